@@ -1,0 +1,206 @@
+"""ctypes front end of the CPU oracle (oracle/tree_attn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports it, and this
+module imports nothing from the product package.
+
+All array arguments are numpy arrays; bfloat16 data travels as uint16 bit
+patterns, fp32 data as float32.  Results are float64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tree_attn_oracle.c")
+_LIB = os.path.join(_HERE, "libets_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (fp64, OpenMP over (leaf, head) only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-ffp-contract=off", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = C.CDLL(_LIB)
+        i32p, i64p, f64p = (C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                            C.POINTER(C.c_double))
+        lib.ets_oracle_threads.restype = C.c_int
+        lib.ets_oracle_check_tree.restype = C.c_int
+        lib.ets_oracle_check_tree.argtypes = [C.c_int32, i32p, i64p, i32p, C.c_int32, i32p,
+                                              C.c_int64]
+        lib.ets_oracle_paths.restype = C.c_int64
+        lib.ets_oracle_paths.argtypes = [C.c_int32, i32p, C.c_int32, i32p, i64p, i32p,
+                                         C.c_int64]
+        lib.ets_oracle_tree_stats.restype = None
+        lib.ets_oracle_tree_stats.argtypes = [C.c_int32, i32p, i32p, C.c_int32, i32p, i64p,
+                                              i64p, i64p, i64p]
+        common = [C.c_int32, i32p, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32,
+                  C.c_int32, C.c_int, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.ets_oracle_attn.restype = C.c_int
+        lib.ets_oracle_attn.argtypes = common + [f64p, f64p]
+        lib.ets_oracle_attn_rows.restype = C.c_int
+        lib.ets_oracle_attn_rows.argtypes = common + [C.c_int64, i32p, i32p, f64p, f64p]
+        lib.ets_oracle_partial.restype = None
+        lib.ets_oracle_partial.argtypes = [C.c_int32, C.c_int32, C.c_int, C.c_double,
+                                           C.c_void_p, C.c_void_p, f64p, C.c_int32,
+                                           C.c_int64, i64p, f64p, f64p, f64p]
+        lib.ets_oracle_merge.restype = None
+        lib.ets_oracle_merge.argtypes = [C.c_int32, C.c_int64, f64p, f64p, f64p, f64p, f64p]
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _vals(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        return a, F32
+    if a.dtype == np.uint16:
+        return a, BF16
+    raise TypeError("values must be float32 or uint16 (bfloat16 bits), got %s" % a.dtype)
+
+
+def threads() -> int:
+    return int(_load().ets_oracle_threads())
+
+
+def check_tree(parent, tok_offset, n_tokens, leaf_node, pool_tokens) -> int:
+    parent, tok_offset, n_tokens, leaf_node = (_i32(parent), _i64(tok_offset),
+                                               _i32(n_tokens), _i32(leaf_node))
+    return int(_load().ets_oracle_check_tree(
+        parent.shape[0], _p(parent, C.c_int32), _p(tok_offset, C.c_int64),
+        _p(n_tokens, C.c_int32), leaf_node.shape[0], _p(leaf_node, C.c_int32),
+        int(pool_tokens)))
+
+
+def paths(parent, leaf_node):
+    """(path_ptr int64 [L+1], path_nodes int32) with each path in root->leaf order."""
+    parent, leaf_node = _i32(parent), _i32(leaf_node)
+    n, L = parent.shape[0], leaf_node.shape[0]
+    cap = max(1, n * max(L, 1))
+    ptr = np.zeros(L + 1, dtype=np.int64)
+    while True:
+        nodes = np.zeros(cap, dtype=np.int32)
+        tot = _load().ets_oracle_paths(n, _p(parent, C.c_int32), L, _p(leaf_node, C.c_int32),
+                                       _p(ptr, C.c_int64), _p(nodes, C.c_int32), cap)
+        if tot >= 0:
+            return ptr, nodes[:tot].copy()
+        cap *= 2
+
+
+def tree_stats(parent, n_tokens, leaf_node):
+    """dict(leaf_count[N], unique_tokens, flat_tokens, live_nodes)."""
+    parent, n_tokens, leaf_node = _i32(parent), _i32(n_tokens), _i32(leaf_node)
+    n = parent.shape[0]
+    cnt = np.zeros(n, dtype=np.int64)
+    u, f, lv = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    _load().ets_oracle_tree_stats(n, _p(parent, C.c_int32), _p(n_tokens, C.c_int32),
+                                  leaf_node.shape[0], _p(leaf_node, C.c_int32),
+                                  _p(cnt, C.c_int64), C.byref(u), C.byref(f), C.byref(lv))
+    return dict(leaf_count=cnt, unique_tokens=u.value, flat_tokens=f.value,
+                live_nodes=lv.value)
+
+
+def _tree_args(parent, tok_offset, n_tokens, leaf_node):
+    parent, tok_offset, n_tokens, leaf_node = (_i32(parent), _i64(tok_offset),
+                                               _i32(n_tokens), _i32(leaf_node))
+    keep = (parent, tok_offset, n_tokens, leaf_node)
+    args = [parent.shape[0], _p(parent, C.c_int32), _p(tok_offset, C.c_int64),
+            _p(n_tokens, C.c_int32), leaf_node.shape[0], _p(leaf_node, C.c_int32)]
+    return keep, args
+
+
+def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
+                     n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
+    """Oracle attention.  k_pool/v_pool: [pool_tokens, Hkv, D]; q: [L, Hq, D].
+
+    rows=None: every (leaf, head) -> out float64 [L, Hq, D], lse float64 [L, Hq].
+    rows=(leaf_idx, head_idx): only those pairs -> out [n, D], lse [n].
+    """
+    k_pool, dt = _vals(k_pool)
+    v_pool, dt2 = _vals(v_pool)
+    q, dt3 = _vals(q)
+    if not (dt == dt2 == dt3):
+        raise TypeError("k, v, q must share one dtype")
+    keep, targs = _tree_args(parent, tok_offset, n_tokens, leaf_node)
+    L = keep[3].shape[0]
+    pool_tokens = k_pool.shape[0]
+    rc = check_tree(*keep, pool_tokens)
+    if rc:
+        raise ValueError("oracle: malformed tree (code %d)" % rc)
+    assert k_pool.shape == v_pool.shape == (pool_tokens, n_kv_heads, head_dim)
+    assert q.shape == (L, n_q_heads, head_dim)
+    common = targs + [n_kv_heads, n_q_heads, head_dim, dt, float(sm_scale),
+                      k_pool.ctypes.data_as(C.c_void_p), v_pool.ctypes.data_as(C.c_void_p),
+                      q.ctypes.data_as(C.c_void_p)]
+    if rows is None:
+        out = np.zeros((L, n_q_heads, head_dim), dtype=np.float64)
+        lse = np.zeros((L, n_q_heads), dtype=np.float64)
+        rc = _load().ets_oracle_attn(*common, _p(out, C.c_double), _p(lse, C.c_double))
+    else:
+        sl, sh = _i32(rows[0]), _i32(rows[1])
+        out = np.zeros((sl.shape[0], head_dim), dtype=np.float64)
+        lse = np.zeros((sl.shape[0],), dtype=np.float64)
+        rc = _load().ets_oracle_attn_rows(*common, sl.shape[0], _p(sl, C.c_int32),
+                                          _p(sh, C.c_int32), _p(out, C.c_double),
+                                          _p(lse, C.c_double))
+    if rc:
+        raise RuntimeError("oracle failed (code %d)" % rc)
+    return out, lse
+
+
+def partial(k_pool, v_pool, qvec, kv_head, rows, sm_scale=0.0):
+    """Unnormalised partial (o[D], m, l) of one query vector over pool rows `rows`."""
+    k_pool, dt = _vals(k_pool)
+    v_pool, _ = _vals(v_pool)
+    qvec = np.ascontiguousarray(qvec, dtype=np.float64)
+    rows = _i64(rows)
+    _, hkv, d = k_pool.shape
+    o = np.zeros(d, dtype=np.float64)
+    m, l = C.c_double(0), C.c_double(0)
+    _load().ets_oracle_partial(hkv, d, dt, float(sm_scale), k_pool.ctypes.data_as(C.c_void_p),
+                               v_pool.ctypes.data_as(C.c_void_p), _p(qvec, C.c_double),
+                               int(kv_head), rows.shape[0], _p(rows, C.c_int64),
+                               _p(o, C.c_double), C.byref(m), C.byref(l))
+    return o, m.value, l.value
+
+
+def merge(o, m, l):
+    """LSE merge of partials o [n, D], m [n], l [n] -> (out [D], lse)."""
+    o = np.ascontiguousarray(o, dtype=np.float64)
+    m = np.ascontiguousarray(m, dtype=np.float64)
+    l = np.ascontiguousarray(l, dtype=np.float64)
+    n, d = o.shape
+    out = np.zeros(d, dtype=np.float64)
+    lse = C.c_double(0)
+    _load().ets_oracle_merge(d, n, _p(o, C.c_double), _p(m, C.c_double), _p(l, C.c_double),
+                             _p(out, C.c_double), C.byref(lse))
+    return out, lse.value

@@ -1,0 +1,213 @@
+"""Seeded generators for search-tree topologies and K/V/Q values.
+
+Topology recipe (stands in for a PRM-guided parallel tree search of width W):
+node 0 is the shared prompt; search step 1 creates W children of the prompt;
+at every later step a weight vector p ~ Dirichlet(alpha * 1_W) over the W nodes
+of the previous step is drawn and the W new nodes pick their parents i.i.d.
+from Categorical(p).  Small alpha concentrates the continuations on few parents
+(heavy KV sharing, like a search that prunes for sharing), large alpha spreads
+them (divergent trajectories).  The leaves are the W nodes of the last step;
+nodes without a leaf beneath them are dead but stay in the parent array.
+
+Step lengths, topology and values come from three independent Philox streams of
+one seed, so two variants that differ only in alpha have identical node lengths.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# configurations
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class TreeConfig:
+    name: str
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+    dtype: str                  # "f32" | "bf16"
+    prompt: int                 # tokens in the shared root
+    steps: int                  # search steps below the root
+    step_lo: int                # step length drawn uniformly in [lo, hi] per node
+    step_hi: int
+    width: int                  # leaves kept per step
+    alpha: Optional[float]      # Dirichlet concentration; None => complete b-ary tree
+    branch: int = 2             # used when alpha is None
+    layers: int = 1
+    store_dead: bool = True     # dead nodes own pool rows (False: they alias row 0)
+    seed: int = 0
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+
+CONFIGS = {
+    # tiny fp32 tree: 1 + 2 + 4 + 8 nodes, 8 leaves, path = 32 + 3*16 = 80 tokens
+    "c1_tiny": TreeConfig("c1_tiny", 1, 2, 64, "f32", 32, 3, 16, 16, 8, None, 2,
+                          seed=1001),
+    "c2_w16": TreeConfig("c2_w16", 8, 32, 128, "bf16", 512, 8, 64, 64, 16, 0.5,
+                         seed=1002),
+    "c3_div": TreeConfig("c3_div", 8, 32, 128, "bf16", 1024, 16, 128, 128, 64, 5.0,
+                         seed=1003),
+    "c3_pruned": TreeConfig("c3_pruned", 8, 32, 128, "bf16", 1024, 16, 128, 128, 64,
+                            0.2, seed=1003),
+    "c4_34b": TreeConfig("c4_34b", 8, 64, 128, "bf16", 2048, 24, 32, 256, 256, 0.3,
+                         store_dead=False, seed=1004),
+    "c5_stress": TreeConfig("c5_stress", 8, 32, 128, "bf16", 4096, 32, 64, 512, 512,
+                            0.3, layers=32, store_dead=False, seed=1005),
+}
+
+
+@dataclass
+class Tree:
+    parent: np.ndarray          # int32 [N], -1 for a root, parent[i] < i
+    tok_offset: np.ndarray      # int64 [N], first pool row of the node
+    n_tokens: np.ndarray        # int32 [N]
+    leaf_node: np.ndarray       # int32 [L], node id of every leaf query
+    pool_tokens: int            # rows in the K/V pool
+    step: np.ndarray = field(default=None)  # int32 [N], search step of the node
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self.parent.shape[0])
+
+    @property
+    def n_leaves(self) -> int:
+        return int(self.leaf_node.shape[0])
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
+
+
+def make_tree(cfg: TreeConfig, seed: Optional[int] = None) -> Tree:
+    """Build the topology of `cfg` (see the module docstring for the recipe)."""
+    seed = cfg.seed if seed is None else seed
+    topo = _rng(seed, 0)
+    lens = _rng(seed, 1)
+
+    parent = [-1]
+    step = [0]
+    prev = np.array([0], dtype=np.int64)
+    for s in range(1, cfg.steps + 1):
+        if cfg.alpha is None:
+            par = np.repeat(prev, cfg.branch)
+        elif s == 1:
+            par = np.zeros(cfg.width, dtype=np.int64)
+        else:
+            p = topo.dirichlet(np.full(prev.shape[0], cfg.alpha, dtype=np.float64))
+            # guard against underflow to an all-zero vector for tiny alpha
+            p = np.maximum(p, 0.0)
+            p = p / p.sum() if p.sum() > 0 else np.full(p.shape, 1.0 / p.shape[0])
+            par = np.sort(prev[topo.choice(prev.shape[0], size=cfg.width, p=p)])
+        first = len(parent)
+        parent.extend(int(x) for x in par)
+        step.extend([s] * len(par))
+        prev = np.arange(first, first + len(par), dtype=np.int64)
+    parent = np.asarray(parent, dtype=np.int32)
+    step = np.asarray(step, dtype=np.int32)
+    n = parent.shape[0]
+
+    n_tokens = lens.integers(cfg.step_lo, cfg.step_hi + 1, size=n).astype(np.int32)
+    n_tokens[0] = cfg.prompt
+    leaf_node = prev.astype(np.int32)
+
+    live = np.zeros(n, dtype=bool)
+    live[leaf_node] = True
+    for i in range(n - 1, 0, -1):
+        if live[i]:
+            live[parent[i]] = True
+
+    stored = np.ones(n, dtype=bool) if cfg.store_dead else live
+    tok_offset = np.zeros(n, dtype=np.int64)
+    sizes = np.where(stored, n_tokens, 0).astype(np.int64)
+    tok_offset[:] = np.cumsum(sizes) - sizes
+    tok_offset[~stored] = 0
+    pool_tokens = int(sizes.sum())
+    return Tree(parent, tok_offset, n_tokens, leaf_node, pool_tokens, step)
+
+
+def random_tree(seed: int, n_nodes: int, n_leaves: int, max_tokens: int,
+                p_root: float = 0.1, p_empty: float = 0.15,
+                shuffle_pool: bool = True) -> Tree:
+    """Irregular forest for fuzzing: random parents (parent[i] < i), several
+    roots, zero-length nodes, leaf entries on interior nodes and duplicated."""
+    r = _rng(seed, 7)
+    parent = np.full(n_nodes, -1, dtype=np.int32)
+    for i in range(1, n_nodes):
+        if r.random() >= p_root:
+            parent[i] = int(r.integers(0, i))
+    n_tokens = r.integers(1, max_tokens + 1, size=n_nodes).astype(np.int32)
+    n_tokens[r.random(n_nodes) < p_empty] = 0
+    order = r.permutation(n_nodes) if shuffle_pool else np.arange(n_nodes)
+    tok_offset = np.zeros(n_nodes, dtype=np.int64)
+    pos = 0
+    for i in order:
+        tok_offset[i] = pos
+        pos += int(n_tokens[i])
+    leaf_node = r.integers(0, n_nodes, size=n_leaves).astype(np.int32)
+    return Tree(parent, tok_offset, n_tokens, leaf_node, max(pos, 1),
+                np.zeros(n_nodes, dtype=np.int32))
+
+
+# --------------------------------------------------------------------------
+# values
+# --------------------------------------------------------------------------
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (round-to-nearest-even); returns uint16 bits."""
+    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    b = b + (np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1)))
+    return (b >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def make_values_host(cfg: TreeConfig, tree: Tree, seed: Optional[int] = None,
+                     layer: int = 0):
+    """K, V: [pool_tokens, Hkv, D]; Q: [L, Hq, D]; i.i.d. N(0,1).
+    float32 arrays for dtype "f32", uint16 bfloat16 bit patterns for "bf16"."""
+    seed = cfg.seed if seed is None else seed
+    r = _rng(seed, 2 + layer)
+    k = r.standard_normal((tree.pool_tokens, cfg.n_kv_heads, cfg.head_dim),
+                          dtype=np.float32)
+    v = r.standard_normal((tree.pool_tokens, cfg.n_kv_heads, cfg.head_dim),
+                          dtype=np.float32)
+    q = r.standard_normal((tree.n_leaves, cfg.n_q_heads, cfg.head_dim),
+                          dtype=np.float32)
+    if cfg.dtype == "bf16":
+        return to_bf16_bits(k), to_bf16_bits(v), to_bf16_bits(q)
+    return k, v, q
+
+
+def make_values_device(cfg: TreeConfig, tree: Tree, device, seed: Optional[int] = None,
+                       layers: Optional[int] = None):
+    """Device-side generation for pools too large to draw on the host.
+    Returns torch tensors K, V: [layers, pool_tokens, Hkv, D], Q: [layers, L, Hq, D]
+    in cfg.dtype, drawn N(0,1) by torch's seeded device generator."""
+    import torch
+    seed = cfg.seed if seed is None else seed
+    layers = cfg.layers if layers is None else layers
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    k = torch.empty((layers, tree.pool_tokens, cfg.n_kv_heads, cfg.head_dim),
+                    dtype=dt, device=device)
+    v = torch.empty_like(k)
+    q = torch.empty((layers, tree.n_leaves, cfg.n_q_heads, cfg.head_dim),
+                    dtype=dt, device=device)
+    for l in range(layers):
+        k[l].normal_(generator=g)
+        v[l].normal_(generator=g)
+        q[l].normal_(generator=g)
+    return k, v, q
