@@ -1,0 +1,186 @@
+/*
+ * libetsattn -- decode attention over a tree-structured KV cache (gfx950).
+ *
+ * The problem, as the ETS paper states it (Sec. 1; Sec. 3, factor 1; Sec. 4.1;
+ * App. B): a PRM-guided parallel tree search keeps a tree whose nodes are
+ * reasoning steps; a trajectory is the chain of step nodes from the root to a
+ * leaf; every trajectory needs the KV state of all of its steps at every
+ * generation step, and trajectories share the KV of their common ancestors.
+ * The size of that shared state -- not FLOPs -- decides the run time because
+ * decoding is memory-bandwidth bound.  This library is the kernel that turns
+ * the sharing into fewer bytes moved: each live node's K/V is read from HBM
+ * once per call for all the leaves beneath it.
+ *
+ * For every leaf query l (node v = leaf_node[l]) and query head j it returns
+ *
+ *     s_t      = sm_scale * <q[l,j,:], K[t,h,:]>   for every pool row t of every
+ *                node on the root->v chain (v included), h = j / (Hq/Hkv)
+ *     lse[l,j] = ln sum_t exp(s_t)                 (natural log)
+ *     out[l,j] = sum_t exp(s_t - lse[l,j]) * V[t,h,:]
+ *
+ * with no mask (the query is the newest position of its trajectory).  A leaf
+ * whose chain holds no tokens gets out = 0 and lse = -inf.
+ *
+ * Conventions
+ *   - Plain C ABI.  "host" / "device" is stated for every pointer.
+ *   - Status codes only; nothing throws or aborts across this boundary and on
+ *     any error the outputs are left untouched.
+ *   - A context is not thread safe; distinct contexts are independent.
+ */
+#ifndef ETSATTN_H
+#define ETSATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ets_ctx ets_ctx; /* opaque */
+
+typedef enum {
+    ETS_OK = 0,
+    ETS_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned buffer            */
+    ETS_ERR_BAD_TREE = 2,    /* parent out of range or >= own index, negative length,      */
+                             /* node rows outside the pool                                 */
+    ETS_ERR_BAD_LEAF = 3,    /* leaf node id out of range                                  */
+    ETS_ERR_UNSUPPORTED = 4, /* shape outside what the kernels are built for               */
+    ETS_ERR_WORKSPACE = 5,   /* workspace smaller than ets_stats.workspace_bytes           */
+    ETS_ERR_NO_PLAN = 6,     /* decode or query before a successful ets_plan               */
+    ETS_ERR_HIP = 7,         /* a HIP runtime call failed, or the context has no device    */
+    ETS_ERR_NOMEM = 8        /* host allocation failed                                     */
+} ets_status;
+
+typedef enum { ETS_F32 = 0, ETS_BF16 = 1 } ets_dtype;
+
+/* Element type and head geometry of the pools and of q.
+ * Supported: head_dim in {64, 128}; n_q_heads = G * n_kv_heads with G in
+ * {1, 2, 4, 8} (query head j reads kv head j / G).  sm_scale <= 0 selects
+ * 1/sqrt(head_dim). */
+typedef struct {
+    int32_t n_kv_heads;
+    int32_t n_q_heads;
+    int32_t head_dim;
+    int32_t dtype; /* ets_dtype of k_pool, v_pool and q */
+    float sm_scale;
+} ets_shape;
+
+/* The search tree (ETS paper Sec. 4.1, App. B).  All arrays are HOST memory,
+ * borrowed for the duration of ets_plan only.
+ *   parent[i]     parent node of i, -1 for a root; parent[i] < i is required
+ *                 (so cycles cannot be expressed); several roots are allowed.
+ *   tok_offset[i] first pool row of node i; the node owns the n_tokens[i]
+ *                 consecutive rows from there.  Nodes may be scattered in the
+ *                 pool in any order; overlap is not checked.
+ *   n_tokens[i]   >= 0; zero-length nodes contribute nothing.
+ *   leaf_node[l]  node of leaf query l.  Any node may be named, interior ones
+ *                 too, and a node may be named several times (a search samples
+ *                 several continuations from one node); each entry has its own
+ *                 query row. */
+typedef struct {
+    int32_t n_nodes;
+    const int32_t* parent;
+    const int64_t* tok_offset;
+    const int32_t* n_tokens;
+    int32_t n_leaves;
+    const int32_t* leaf_node;
+} ets_tree;
+
+/* Statistics of the current plan.  unique_* counts the tokens of live nodes
+ * (nodes with a leaf query at or beneath them) once; flat_* sums every leaf's
+ * own chain -- what a kernel without tree awareness would read.  Bytes are K
+ * plus V over all kv heads for ONE layer.  This is the per-tree analogue of
+ * the paper's "KV size" proxy (Sec. 3), which sums it over the search steps. */
+typedef struct {
+    int64_t n_nodes;
+    int64_t live_nodes;
+    int64_t n_leaves;
+    int64_t unique_tokens;
+    int64_t flat_tokens;
+    int64_t unique_kv_bytes;
+    int64_t flat_kv_bytes;
+    int64_t n_segments;      /* chains of live nodes with identical leaf sets            */
+    int64_t n_partials;      /* partial results per query head, summed over the leaves   */
+    int64_t n_stream_items;  /* work items of the per-leaf streaming kernel              */
+    int64_t n_cascade_items; /* work items of the shared-node kernel                     */
+    int64_t min_pool_tokens; /* pools must hold at least this many rows                  */
+    int64_t workspace_bytes; /* device scratch ets_tree_decode_attn needs                */
+} ets_stats;
+
+typedef enum {
+    ETS_PLAN_TREE = 0, /* every live node is read once for all leaves beneath it        */
+    ETS_PLAN_FLAT = 1  /* baseline: every leaf streams its whole chain by itself        */
+} ets_plan_mode;
+
+/* Creates a context for one head geometry on HIP device `hip_device`.
+ * hip_device < 0 creates a host-only context: planning and the plan queries
+ * work, ets_tree_decode_attn returns ETS_ERR_HIP.  *out is set only on ETS_OK
+ * and is released with ets_destroy (NULL is accepted). */
+ets_status ets_create(ets_ctx** out, const ets_shape* shape, int hip_device);
+void ets_destroy(ets_ctx* ctx);
+
+/* Integer planning, once per search step (the topology changes only when the
+ * search prunes or expands: ETS paper Sec. 4.1).  Validates the tree, counts
+ * the leaf queries beneath every node, merges chains of nodes with identical
+ * leaf sets into segments, cuts the segments into work items and numbers the
+ * partial results.  Copies what it needs: the caller's arrays are not
+ * referenced after return.  On a device context the index arrays are uploaded
+ * to device memory owned by the context; the call waits for the stream last
+ * used with this context before it replaces them.  On error the previous plan
+ * is dropped. */
+ets_status ets_plan(ets_ctx* ctx, const ets_tree* tree, int mode /* ets_plan_mode */);
+
+ets_status ets_plan_stats(const ets_ctx* ctx, ets_stats* out /* host */);
+
+/* Root->leaf node chains of the planned tree in CSR form, for checking the
+ * planner's indexing bit for bit: path_ptr[n_leaves + 1], path_nodes[cap]
+ * (host).  *n_path_nodes (may be NULL) receives the total; if it exceeds cap
+ * nothing is written to path_nodes and ETS_ERR_INVALID_ARG is returned. */
+ets_status ets_plan_paths(const ets_ctx* ctx, int64_t* path_ptr, int32_t* path_nodes,
+                          int64_t cap, int64_t* n_path_nodes);
+
+/* leaf_count[n_nodes] (host): number of leaf queries at or beneath each node. */
+ets_status ets_plan_leaf_counts(const ets_ctx* ctx, int64_t* leaf_count);
+
+/* Pool rows the planned work items read on behalf of leaf query `leaf`, in
+ * the order of its partial results: rows[cap] (host).  *n_rows and
+ * *n_partials (either may be NULL) receive the counts.  With a correct plan
+ * the rows are exactly the leaf's chain, root first, each row once. */
+ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, int64_t cap,
+                               int64_t* n_rows, int32_t* n_partials);
+
+/* Planner knobs, effective from the next ets_plan.  Keys:
+ *   "stream_chunk"   max tokens per work item of the streaming kernel (0 = auto)
+ *   "cascade_chunk"  max tokens per work item of the shared-node kernel (0 = auto)
+ *   "cascade_min_leaves"  a segment shared by at least this many leaf queries is
+ *                    read once by the shared-node kernel; below it every leaf
+ *                    streams the segment itself (default 2; 0 disables the
+ *                    shared-node kernel)
+ * Unknown key or negative value: ETS_ERR_INVALID_ARG. */
+ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
+
+/* One layer of decode attention for every leaf query of the planned tree.
+ *   k_pool, v_pool  DEVICE, [pool_tokens][n_kv_heads][head_dim] of shape.dtype,
+ *                   16-byte aligned; pool_tokens >= stats.min_pool_tokens
+ *   q               DEVICE, [n_leaves][n_q_heads][head_dim] of shape.dtype, 16-byte aligned
+ *   out             DEVICE, [n_leaves][n_q_heads][head_dim] float
+ *   lse             DEVICE, [n_leaves][n_q_heads] float
+ *   workspace       DEVICE, >= stats.workspace_bytes, 16-byte aligned, contents
+ *                   undefined before and after; may be NULL when that is 0
+ *   hip_stream      hipStream_t (NULL = the default stream) of the context's device
+ * The call only enqueues kernels on hip_stream: it does not synchronise and
+ * does not allocate.  All buffers stay owned by the caller and must stay valid
+ * until the stream has passed the call.  A plan may be reused for any number
+ * of calls (layers, decode steps) while the tree is unchanged.  The result is
+ * bitwise reproducible from run to run (no floating-point atomics). */
+ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                int64_t pool_tokens, const void* q, float* out, float* lse,
+                                void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* Static string for a status code. */
+const char* ets_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ETSATTN_H */

@@ -1,0 +1,233 @@
+"""ctypes binding of include/etsattn.h.  Same names, same order of arguments;
+numpy arrays stand for host pointers, torch tensors (or integer addresses) for
+device pointers."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+ETS_F32, ETS_BF16 = 0, 1
+ETS_PLAN_TREE, ETS_PLAN_FLAT = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libetsattn.so")
+_lib = None
+
+
+class EtsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, ets_strerror(status), status))
+
+
+class EtsShape(C.Structure):
+    _fields_ = [("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("sm_scale", C.c_float)]
+
+
+class _EtsTree(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("parent", C.POINTER(C.c_int32)),
+                ("tok_offset", C.POINTER(C.c_int64)), ("n_tokens", C.POINTER(C.c_int32)),
+                ("n_leaves", C.c_int32), ("leaf_node", C.POINTER(C.c_int32))]
+
+
+class EtsStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "n_nodes", "live_nodes", "n_leaves", "unique_tokens", "flat_tokens", "unique_kv_bytes",
+        "flat_kv_bytes", "n_segments", "n_partials", "n_stream_items", "n_cascade_items",
+        "min_pool_tokens", "workspace_bytes")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libetsattn.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "libetsattn.so is not built: run `python -m paper_2502_13575_amd.build` "
+            "(there is no CPU fallback for the attention path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp = C.c_void_p
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    lib.ets_create.restype = C.c_int
+    lib.ets_create.argtypes = [C.POINTER(vp), C.POINTER(EtsShape), C.c_int]
+    lib.ets_destroy.restype = None
+    lib.ets_destroy.argtypes = [vp]
+    lib.ets_plan.restype = C.c_int
+    lib.ets_plan.argtypes = [vp, C.POINTER(_EtsTree), C.c_int]
+    lib.ets_plan_stats.restype = C.c_int
+    lib.ets_plan_stats.argtypes = [vp, C.POINTER(EtsStats)]
+    lib.ets_plan_paths.restype = C.c_int
+    lib.ets_plan_paths.argtypes = [vp, i64p, i32p, C.c_int64, i64p]
+    lib.ets_plan_leaf_counts.restype = C.c_int
+    lib.ets_plan_leaf_counts.argtypes = [vp, i64p]
+    lib.ets_plan_leaf_cover.restype = C.c_int
+    lib.ets_plan_leaf_cover.argtypes = [vp, C.c_int32, i64p, C.c_int64, i64p, i32p]
+    lib.ets_set_option.restype = C.c_int
+    lib.ets_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+    lib.ets_tree_decode_attn.restype = C.c_int
+    lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
+    lib.ets_strerror.restype = C.c_char_p
+    lib.ets_strerror.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise EtsError(status, where)
+
+
+def _dev_ptr(x):
+    """Device address of a torch tensor, or an integer address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return C.c_void_p(x)
+    return C.c_void_p(x.data_ptr())
+
+
+def ets_strerror(status: int) -> str:
+    return load_library().ets_strerror(int(status)).decode()
+
+
+def ets_create(shape: EtsShape, hip_device: int):
+    ctx = C.c_void_p()
+    _check(load_library().ets_create(C.byref(ctx), C.byref(shape), int(hip_device)), "ets_create")
+    return ctx
+
+
+def ets_destroy(ctx):
+    load_library().ets_destroy(ctx)
+
+
+def ets_set_option(ctx, key: str, value: int):
+    _check(load_library().ets_set_option(ctx, key.encode(), int(value)), "ets_set_option")
+
+
+def ets_plan(ctx, parent, tok_offset, n_tokens, leaf_node, mode: int = ETS_PLAN_TREE):
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    tok_offset = np.ascontiguousarray(tok_offset, dtype=np.int64)
+    n_tokens = np.ascontiguousarray(n_tokens, dtype=np.int32)
+    leaf_node = np.ascontiguousarray(leaf_node, dtype=np.int32)
+    if not (parent.shape == tok_offset.shape == n_tokens.shape):
+        raise ValueError("parent, tok_offset and n_tokens must have one length")
+    t = _EtsTree(parent.shape[0], parent.ctypes.data_as(C.POINTER(C.c_int32)),
+                 tok_offset.ctypes.data_as(C.POINTER(C.c_int64)),
+                 n_tokens.ctypes.data_as(C.POINTER(C.c_int32)), leaf_node.shape[0],
+                 leaf_node.ctypes.data_as(C.POINTER(C.c_int32)))
+    _check(load_library().ets_plan(ctx, C.byref(t), int(mode)), "ets_plan")
+
+
+def ets_plan_stats(ctx) -> EtsStats:
+    st = EtsStats()
+    _check(load_library().ets_plan_stats(ctx, C.byref(st)), "ets_plan_stats")
+    return st
+
+
+def ets_plan_paths(ctx):
+    """(path_ptr int64 [L+1], path_nodes int32 [total]) in root->leaf order."""
+    lib = load_library()
+    st = ets_plan_stats(ctx)
+    ptr = np.zeros(st.n_leaves + 1, dtype=np.int64)
+    total = C.c_int64(0)
+    rc = lib.ets_plan_paths(ctx, ptr.ctypes.data_as(C.POINTER(C.c_int64)), None, 0,
+                            C.byref(total))
+    if rc != 0 and total.value == 0:
+        _check(rc, "ets_plan_paths")
+    nodes = np.zeros(max(total.value, 1), dtype=np.int32)
+    _check(lib.ets_plan_paths(ctx, ptr.ctypes.data_as(C.POINTER(C.c_int64)),
+                              nodes.ctypes.data_as(C.POINTER(C.c_int32)), nodes.shape[0],
+                              C.byref(total)), "ets_plan_paths")
+    return ptr, nodes[:total.value].copy()
+
+
+def ets_plan_leaf_counts(ctx):
+    st = ets_plan_stats(ctx)
+    cnt = np.zeros(max(st.n_nodes, 1), dtype=np.int64)
+    _check(load_library().ets_plan_leaf_counts(ctx, cnt.ctypes.data_as(C.POINTER(C.c_int64))),
+           "ets_plan_leaf_counts")
+    return cnt[:st.n_nodes].copy()
+
+
+def ets_plan_leaf_cover(ctx, leaf: int):
+    """(rows int64 [n], n_partials) read for one leaf query, in partial order."""
+    lib = load_library()
+    n, npart = C.c_int64(0), C.c_int32(0)
+    rc = lib.ets_plan_leaf_cover(ctx, int(leaf), None, 0, C.byref(n), C.byref(npart))
+    if rc != 0 and not (rc == 1 and n.value > 0):
+        _check(rc, "ets_plan_leaf_cover")
+    rows = np.zeros(max(n.value, 1), dtype=np.int64)
+    _check(lib.ets_plan_leaf_cover(ctx, int(leaf), rows.ctypes.data_as(C.POINTER(C.c_int64)),
+                                   rows.shape[0], C.byref(n), C.byref(npart)),
+           "ets_plan_leaf_cover")
+    return rows[:n.value].copy(), int(npart.value)
+
+
+def ets_tree_decode_attn(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse, workspace,
+                         workspace_bytes: int, hip_stream=None):
+    stream = None if hip_stream is None else C.c_void_p(int(hip_stream))
+    _check(load_library().ets_tree_decode_attn(
+        ctx, _dev_ptr(k_pool), _dev_ptr(v_pool), int(pool_tokens), _dev_ptr(q), _dev_ptr(out),
+        _dev_ptr(lse), _dev_ptr(workspace), int(workspace_bytes), stream),
+        "ets_tree_decode_attn")
+
+
+class Context:
+    """Owns one ets_ctx.  Thin convenience over the functions above."""
+
+    def __init__(self, n_kv_heads: int, n_q_heads: int, head_dim: int, dtype: int,
+                 hip_device: int, sm_scale: float = 0.0):
+        self.shape = EtsShape(n_kv_heads, n_q_heads, head_dim, dtype, sm_scale)
+        self._ctx = ets_create(self.shape, hip_device)
+
+    def close(self):
+        if self._ctx is not None:
+            ets_destroy(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def set_option(self, key, value):
+        ets_set_option(self._ctx, key, value)
+
+    def plan(self, parent, tok_offset, n_tokens, leaf_node, mode=ETS_PLAN_TREE) -> EtsStats:
+        ets_plan(self._ctx, parent, tok_offset, n_tokens, leaf_node, mode)
+        return ets_plan_stats(self._ctx)
+
+    def stats(self) -> EtsStats:
+        return ets_plan_stats(self._ctx)
+
+    def paths(self):
+        return ets_plan_paths(self._ctx)
+
+    def leaf_counts(self):
+        return ets_plan_leaf_counts(self._ctx)
+
+    def leaf_cover(self, leaf):
+        return ets_plan_leaf_cover(self._ctx, leaf)
+
+    def decode(self, k_pool, v_pool, pool_tokens, q, out, lse, workspace, workspace_bytes,
+               hip_stream=None):
+        ets_tree_decode_attn(self._ctx, k_pool, v_pool, pool_tokens, q, out, lse, workspace,
+                             workspace_bytes, hip_stream)

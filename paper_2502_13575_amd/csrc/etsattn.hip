@@ -1,0 +1,339 @@
+// C ABI of libetsattn (see include/etsattn.h) and the kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "etsattn.h"
+#include "merge_kernel.hpp"
+#include "plan.h"
+#include "stream_kernel.hpp"
+
+using namespace ets;
+
+struct ets_ctx {
+    ets_shape shape{};
+    float scale = 0.f;
+    int device = -1;
+    PlanOptions opt;
+    Plan plan;
+    // device copies of the plan's index arrays, carved out of one allocation
+    char* d_buf = nullptr;
+    size_t d_cap = 0;
+    Run* d_runs = nullptr;
+    StreamItem* d_stream = nullptr;
+    CascadeItem* d_cascade = nullptr;
+    int32_t* d_ent_order = nullptr;
+    int32_t* d_part_base = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool stream_used = false;
+};
+
+namespace {
+
+// Makes the context's device current for the scope of a call.
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) {
+            ok = false;
+            return;
+        }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        target = dev;
+    }
+    ~DeviceGuard() {
+        if (ok && prev != target) (void)hipSetDevice(prev);
+    }
+    int target = -1;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool shape_supported(const ets_shape& s) {
+    if (s.n_kv_heads <= 0 || s.n_q_heads <= 0) return false;
+    if (s.head_dim != 64 && s.head_dim != 128) return false;
+    if (s.dtype != ETS_F32 && s.dtype != ETS_BF16) return false;
+    if (s.n_q_heads % s.n_kv_heads != 0) return false;
+    const int g = s.n_q_heads / s.n_kv_heads;
+    return g == 1 || g == 2 || g == 4 || g == 8;
+}
+
+ets_status upload_plan(ets_ctx* c) {
+    const Plan& p = c->plan;
+    const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
+    const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
+    const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
+    const size_t b_ent = align_up(p.ent_order.size() * sizeof(int32_t), 256);
+    const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
+    const size_t total = b_runs + b_stream + b_casc + b_ent + b_base + 256;
+
+    std::vector<char> stage(total, 0);
+    size_t off = 0;
+    auto put = [&](const void* src, size_t bytes, size_t padded) {
+        if (bytes) std::memcpy(stage.data() + off, src, bytes);
+        const size_t at = off;
+        off += padded;
+        return at;
+    };
+    const size_t o_runs = put(p.runs.data(), p.runs.size() * sizeof(Run), b_runs);
+    const size_t o_stream =
+        put(p.stream_items.data(), p.stream_items.size() * sizeof(StreamItem), b_stream);
+    const size_t o_casc =
+        put(p.cascade_items.data(), p.cascade_items.size() * sizeof(CascadeItem), b_casc);
+    const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
+    const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
+
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    if (c->stream_used && hipStreamSynchronize(c->last_stream) != hipSuccess) return ETS_ERR_HIP;
+    if (total > c->d_cap) {
+        if (c->d_buf) (void)hipFree(c->d_buf);
+        c->d_buf = nullptr;
+        c->d_cap = 0;
+        const size_t want = align_up(total + total / 2, 4096);
+        if (hipMalloc(reinterpret_cast<void**>(&c->d_buf), want) != hipSuccess) {
+            (void)hipGetLastError();
+            return ETS_ERR_HIP;
+        }
+        c->d_cap = want;
+    }
+    if (hipMemcpy(c->d_buf, stage.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        return ETS_ERR_HIP;
+    }
+    c->d_runs = reinterpret_cast<Run*>(c->d_buf + o_runs);
+    c->d_stream = reinterpret_cast<StreamItem*>(c->d_buf + o_stream);
+    c->d_cascade = reinterpret_cast<CascadeItem*>(c->d_buf + o_casc);
+    c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
+    c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
+    return ETS_OK;
+}
+
+struct LaunchArgs {
+    const void *k, *v, *q;
+    float* out;
+    float* lse;
+    float* ws_o;
+    float2* ws_ml;
+    hipStream_t stream;
+};
+
+template <typename T, int D, int G>
+void launch_stream(const ets_ctx* c, const LaunchArgs& a) {
+    constexpr int U = (G >= 8) ? 2 : 4;
+    const int64_t n_items = (int64_t)c->plan.stream_items.size();
+    if (n_items == 0) return;
+    const unsigned grid = (unsigned)(n_items * c->shape.n_kv_heads);
+    hipLaunchKernelGGL((stream_attn_kernel<T, D, G, U>), dim3(grid), dim3(64), 0, a.stream,
+                       static_cast<const T*>(a.k), static_cast<const T*>(a.v),
+                       static_cast<const T*>(a.q), c->d_runs, c->d_stream, c->shape.n_kv_heads,
+                       c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+}
+
+template <typename T, int D>
+void launch_stream_g(const ets_ctx* c, const LaunchArgs& a) {
+    switch (c->shape.n_q_heads / c->shape.n_kv_heads) {
+        case 1: launch_stream<T, D, 1>(c, a); break;
+        case 2: launch_stream<T, D, 2>(c, a); break;
+        case 4: launch_stream<T, D, 4>(c, a); break;
+        default: launch_stream<T, D, 8>(c, a); break;
+    }
+}
+
+void launch_all(const ets_ctx* c, const LaunchArgs& a) {
+    const bool bf = c->shape.dtype == ETS_BF16;
+    if (c->shape.head_dim == 128) {
+        if (bf) launch_stream_g<bf16_t, 128>(c, a);
+        else launch_stream_g<float, 128>(c, a);
+    } else {
+        if (bf) launch_stream_g<bf16_t, 64>(c, a);
+        else launch_stream_g<float, 64>(c, a);
+    }
+    const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
+    if (pairs == 0) return;
+    const unsigned grid = (unsigned)((pairs + 3) / 4);
+    if (c->shape.head_dim == 128)
+        hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, (int)c->plan.stats.n_leaves, c->shape.n_q_heads,
+                           a.ws_o, a.ws_ml, a.out, a.lse);
+    else
+        hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, (int)c->plan.stats.n_leaves, c->shape.n_q_heads,
+                           a.ws_o, a.ws_ml, a.out, a.lse);
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+ets_status ets_create(ets_ctx** out, const ets_shape* shape, int hip_device) {
+    if (!out || !shape) return ETS_ERR_INVALID_ARG;
+    if (!shape_supported(*shape)) return ETS_ERR_UNSUPPORTED;
+    if (hip_device >= 0) {
+        int n = 0;
+        if (hipGetDeviceCount(&n) != hipSuccess) {
+            (void)hipGetLastError();
+            return ETS_ERR_HIP;
+        }
+        if (hip_device >= n) return ETS_ERR_INVALID_ARG;
+    }
+    ets_ctx* c = new (std::nothrow) ets_ctx();
+    if (!c) return ETS_ERR_NOMEM;
+    c->shape = *shape;
+    c->scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / std::sqrt((float)shape->head_dim);
+    c->device = hip_device < 0 ? -1 : hip_device;
+    *out = c;
+    return ETS_OK;
+}
+
+void ets_destroy(ets_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->d_buf) {
+        DeviceGuard guard(ctx->device);
+        if (guard.ok) {
+            if (ctx->stream_used) (void)hipStreamSynchronize(ctx->last_stream);
+            (void)hipFree(ctx->d_buf);
+        }
+    }
+    delete ctx;
+}
+
+ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
+    if (!ctx || !key || value < 0) return ETS_ERR_INVALID_ARG;
+    if (!std::strcmp(key, "stream_chunk")) ctx->opt.stream_chunk = value;
+    else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
+    else if (!std::strcmp(key, "cascade_min_leaves")) ctx->opt.cascade_min_leaves = value;
+    else return ETS_ERR_INVALID_ARG;
+    return ETS_OK;
+}
+
+ets_status ets_plan(ets_ctx* ctx, const ets_tree* tree, int mode) {
+    if (!ctx || !tree) return ETS_ERR_INVALID_ARG;
+    ets_status s = build_plan(ctx->shape, ctx->opt, *tree, mode, ctx->plan);
+    if (s != ETS_OK) return s;
+    if (ctx->device >= 0) {
+        s = upload_plan(ctx);
+        if (s != ETS_OK) ctx->plan.valid = false;
+    }
+    return s;
+}
+
+ets_status ets_plan_stats(const ets_ctx* ctx, ets_stats* out) {
+    if (!ctx || !out) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    *out = ctx->plan.stats;
+    return ETS_OK;
+}
+
+ets_status ets_plan_paths(const ets_ctx* ctx, int64_t* path_ptr, int32_t* path_nodes, int64_t cap,
+                          int64_t* n_path_nodes) {
+    if (!ctx || !path_ptr || cap < 0 || (cap > 0 && !path_nodes)) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    const Plan& p = ctx->plan;
+    const int32_t L = (int32_t)p.stats.n_leaves;
+    try {
+        std::vector<int32_t> all;
+        std::vector<int64_t> ptr((size_t)L + 1, 0);
+        for (int32_t l = 0; l < L; ++l) {
+            chain_of(p, l, all);
+            ptr[l + 1] = (int64_t)all.size();
+        }
+        if (n_path_nodes) *n_path_nodes = (int64_t)all.size();
+        if ((int64_t)all.size() > cap) return ETS_ERR_INVALID_ARG;
+        std::memcpy(path_ptr, ptr.data(), ptr.size() * sizeof(int64_t));
+        if (!all.empty()) std::memcpy(path_nodes, all.data(), all.size() * sizeof(int32_t));
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+    return ETS_OK;
+}
+
+ets_status ets_plan_leaf_counts(const ets_ctx* ctx, int64_t* leaf_count) {
+    if (!ctx || !leaf_count) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    const Plan& p = ctx->plan;
+    if (!p.leaf_count.empty())
+        std::memcpy(leaf_count, p.leaf_count.data(), p.leaf_count.size() * sizeof(int64_t));
+    return ETS_OK;
+}
+
+ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, int64_t cap,
+                               int64_t* n_rows, int32_t* n_partials) {
+    if (!ctx || cap < 0 || (cap > 0 && !rows)) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    if (leaf < 0 || leaf >= ctx->plan.stats.n_leaves) return ETS_ERR_BAD_LEAF;
+    try {
+        std::vector<int64_t> r;
+        int32_t np = 0;
+        const bool ok = leaf_cover(ctx->plan, leaf, r, np);
+        if (n_rows) *n_rows = (int64_t)r.size();
+        if (n_partials) *n_partials = np;
+        if (!ok) return ETS_ERR_BAD_TREE;
+        if ((int64_t)r.size() > cap) return ETS_ERR_INVALID_ARG;
+        if (!r.empty()) std::memcpy(rows, r.data(), r.size() * sizeof(int64_t));
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+    return ETS_OK;
+}
+
+ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                int64_t pool_tokens, const void* q, float* out, float* lse,
+                                void* workspace, int64_t workspace_bytes, void* hip_stream) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    const ets_stats& st = ctx->plan.stats;
+    if (st.n_leaves == 0) return ETS_OK;
+    if (!q || !out || !lse || pool_tokens < 0 || workspace_bytes < 0) return ETS_ERR_INVALID_ARG;
+    if (st.unique_tokens > 0 && (!k_pool || !v_pool)) return ETS_ERR_INVALID_ARG;
+    if (pool_tokens < st.min_pool_tokens) return ETS_ERR_BAD_TREE;
+    if (workspace_bytes < st.workspace_bytes || (st.workspace_bytes > 0 && !workspace))
+        return ETS_ERR_WORKSPACE;
+    if (misaligned(k_pool) || misaligned(v_pool) || misaligned(q) || misaligned(out) ||
+        misaligned(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return ETS_ERR_INVALID_ARG;
+
+    if (!ctx->plan.cascade_items.empty()) return ETS_ERR_UNSUPPORTED;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    LaunchArgs a;
+    a.k = k_pool;
+    a.v = v_pool;
+    a.q = q;
+    a.out = out;
+    a.lse = lse;
+    a.ws_o = static_cast<float*>(workspace);
+    a.ws_ml = reinterpret_cast<float2*>(a.ws_o + st.n_partials * ctx->shape.n_q_heads *
+                                                     (int64_t)ctx->shape.head_dim);
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    launch_all(ctx, a);
+    ctx->last_stream = a.stream;
+    ctx->stream_used = true;
+    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    return ETS_OK;
+}
+
+const char* ets_strerror(int status) {
+    switch (status) {
+        case ETS_OK: return "ok";
+        case ETS_ERR_INVALID_ARG: return "invalid argument";
+        case ETS_ERR_BAD_TREE: return "malformed tree";
+        case ETS_ERR_BAD_LEAF: return "leaf node id out of range";
+        case ETS_ERR_UNSUPPORTED: return "unsupported shape";
+        case ETS_ERR_WORKSPACE: return "workspace too small";
+        case ETS_ERR_NO_PLAN: return "no plan";
+        case ETS_ERR_HIP: return "HIP runtime error or host-only context";
+        case ETS_ERR_NOMEM: return "out of host memory";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,380 @@
+// Host planner: validates the tree, counts leaf queries per node, compacts
+// chains of nodes with identical leaf sets into segments, cuts segments into
+// work items for the two attention kernels and numbers the partial results.
+//
+// Tree semantics after the ETS paper, Sec. 4.1 and App. B: a non-leaf node is
+// needed iff some retained leaf is among its descendants, and all trajectories
+// through a node share that node's KV.
+#include "plan.h"
+
+#include <algorithm>
+#include <limits>
+#include <new>
+
+namespace ets {
+namespace {
+
+struct Seg {
+    int32_t parent_seg = -1;
+    int64_t cnt = 0;             // leaf queries at or beneath the segment
+    std::vector<int32_t> nodes;  // chain, root side first
+    int64_t tokens = 0;
+    int32_t ent_begin = 0;       // range in Plan::ent_order
+    int32_t own_filled = 0;
+    int32_t child_cursor = 0;
+    int32_t prefix = 0;          // partial slots used by the segments above
+    int32_t n_chunks = 0;
+    bool cascade = false;
+};
+
+struct Chunk {
+    int32_t run_begin, run_end, tokens;
+};
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
+
+// Appends the (merged) pool runs of a node list to `out`.
+void collect_runs(const Plan& p, const std::vector<int32_t>& nodes, std::vector<Run>& out) {
+    for (int32_t n : nodes) {
+        const int32_t len = p.n_tokens[n];
+        if (len <= 0) continue;
+        const int64_t tok = p.tok_offset[n];
+        if (!out.empty() && out.back().tok + out.back().n == tok &&
+            (int64_t)out.back().n + len <= std::numeric_limits<int32_t>::max()) {
+            out.back().n += len;
+        } else {
+            out.push_back(Run{tok, len, 0});
+        }
+    }
+}
+
+// Cuts `src` (total `tokens` rows) into pieces of at most `cap` rows, sized
+// evenly in multiples of 32 rows, appending the pieces' runs to plan.runs.
+void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
+              std::vector<Chunk>& chunks) {
+    chunks.clear();
+    if (tokens <= 0) return;
+    cap = std::max<int64_t>(cap, 32);
+    int64_t n_chunks = ceil_div(tokens, cap);
+    int64_t per = std::min(cap, round_up(ceil_div(tokens, n_chunks), 32));
+    size_t ri = 0;
+    int64_t used = 0;  // rows of src[ri] already handed out
+    int64_t left = tokens;
+    while (left > 0) {
+        int64_t want = std::min(per, left);
+        Chunk c{(int32_t)p.runs.size(), 0, (int32_t)want};
+        while (want > 0) {
+            const int64_t avail = src[ri].n - used;
+            const int64_t take = std::min(avail, want);
+            p.runs.push_back(Run{src[ri].tok + used, (int32_t)take, 0});
+            used += take;
+            want -= take;
+            if (used == src[ri].n) {
+                ++ri;
+                used = 0;
+            }
+        }
+        c.run_end = (int32_t)p.runs.size();
+        left -= c.tokens;
+        chunks.push_back(c);
+    }
+}
+
+ets_status validate(const ets_tree& t) {
+    if (t.n_nodes < 0 || t.n_leaves < 0) return ETS_ERR_INVALID_ARG;
+    if (t.n_nodes > 0 && (!t.parent || !t.tok_offset || !t.n_tokens)) return ETS_ERR_INVALID_ARG;
+    if (t.n_leaves > 0 && !t.leaf_node) return ETS_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < t.n_nodes; ++i) {
+        if (t.parent[i] < -1 || t.parent[i] >= i) return ETS_ERR_BAD_TREE;
+        if (t.n_tokens[i] < 0 || t.tok_offset[i] < 0) return ETS_ERR_BAD_TREE;
+        if (t.tok_offset[i] > std::numeric_limits<int64_t>::max() - t.n_tokens[i])
+            return ETS_ERR_BAD_TREE;
+    }
+    for (int32_t l = 0; l < t.n_leaves; ++l)
+        if (t.leaf_node[l] < 0 || t.leaf_node[l] >= t.n_nodes) return ETS_ERR_BAD_LEAF;
+    return ETS_OK;
+}
+
+ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree& tree, int mode,
+                 Plan& p) {
+    const int32_t N = tree.n_nodes, L = tree.n_leaves;
+    const int32_t G = shape.n_q_heads / shape.n_kv_heads;
+    const int64_t esz = shape.dtype == ETS_F32 ? 4 : 2;
+
+    p.mode = mode;
+    p.parent.assign(tree.parent, tree.parent + N);
+    p.tok_offset.assign(tree.tok_offset, tree.tok_offset + N);
+    p.n_tokens.assign(tree.n_tokens, tree.n_tokens + N);
+    p.leaf_node.assign(tree.leaf_node, tree.leaf_node + L);
+
+    // leaf queries at or beneath every node (children have larger ids)
+    std::vector<int64_t> own(N, 0);
+    for (int32_t l = 0; l < L; ++l) own[p.leaf_node[l]] += 1;
+    p.leaf_count = own;
+    for (int32_t i = N - 1; i >= 0; --i)
+        if (p.parent[i] >= 0) p.leaf_count[p.parent[i]] += p.leaf_count[i];
+
+    ets_stats& st = p.stats;
+    st = ets_stats{};
+    st.n_nodes = N;
+    st.n_leaves = L;
+    for (int32_t i = 0; i < N; ++i) {
+        if (p.leaf_count[i] == 0) continue;
+        st.live_nodes += 1;
+        st.unique_tokens += p.n_tokens[i];
+        st.flat_tokens += p.leaf_count[i] * (int64_t)p.n_tokens[i];
+        if (p.n_tokens[i] > 0)
+            st.min_pool_tokens = std::max(st.min_pool_tokens, p.tok_offset[i] + p.n_tokens[i]);
+    }
+    const int64_t tok_bytes = 2 * (int64_t)shape.n_kv_heads * shape.head_dim * esz;
+    st.unique_kv_bytes = st.unique_tokens * tok_bytes;
+    st.flat_kv_bytes = st.flat_tokens * tok_bytes;
+
+    // chain compaction: a live node joins its parent's segment when both have
+    // the same leaf set, i.e. the same count
+    std::vector<Seg> segs;
+    std::vector<int32_t> seg_of(N, -1);
+    for (int32_t i = 0; i < N; ++i) {
+        if (p.leaf_count[i] == 0) continue;
+        const int32_t par = p.parent[i];
+        if (par >= 0 && p.leaf_count[par] == p.leaf_count[i]) {
+            seg_of[i] = seg_of[par];
+        } else {
+            Seg s;
+            s.parent_seg = par >= 0 ? seg_of[par] : -1;
+            s.cnt = p.leaf_count[i];
+            seg_of[i] = (int32_t)segs.size();
+            segs.push_back(std::move(s));
+        }
+        Seg& s = segs[seg_of[i]];
+        s.nodes.push_back(i);
+        s.tokens += p.n_tokens[i];
+    }
+    st.n_segments = (int64_t)segs.size();
+
+    p.runs.clear();
+    p.stream_items.clear();
+    p.cascade_items.clear();
+    p.ent_order.assign(L, 0);
+    p.part_base.assign((size_t)L + 1, 0);
+    p.max_cascade_ent = 0;
+
+    std::vector<Run> tmp_runs;
+    std::vector<Chunk> chunks;
+    std::vector<int32_t> stream_tokens;   // per stream item, for ordering
+    std::vector<int64_t> cascade_cost;    // per cascade item, for ordering
+
+    // leaf queries in depth-first segment order: the queries beneath a segment
+    // form one contiguous range of ent_order
+    {
+        std::vector<int64_t> seg_own(segs.size(), 0);
+        for (int32_t l = 0; l < L; ++l) seg_own[seg_of[p.leaf_node[l]]] += 1;
+        int64_t root_cursor = 0;
+        for (size_t s = 0; s < segs.size(); ++s) {
+            Seg& sg = segs[s];
+            if (sg.parent_seg < 0) {
+                sg.ent_begin = (int32_t)root_cursor;
+                root_cursor += sg.cnt;
+            } else {
+                Seg& ps = segs[sg.parent_seg];
+                sg.ent_begin = ps.child_cursor;
+                ps.child_cursor += (int32_t)sg.cnt;
+            }
+            sg.child_cursor = sg.ent_begin + (int32_t)seg_own[s];
+        }
+        for (int32_t l = 0; l < L; ++l) {
+            Seg& sg = segs[seg_of[p.leaf_node[l]]];
+            p.ent_order[sg.ent_begin + sg.own_filled++] = l;
+        }
+    }
+
+    // Which kernel reads which segment.  The shared-node kernel reads a segment
+    // once for all `cnt` leaf queries beneath it but costs one partial result per
+    // query and query head (written, then read by the merge); otherwise every
+    // query streams the segment itself as part of its own item.  A segment goes
+    // to the shared-node kernel when the KV bytes it saves exceed the partial
+    // bytes it adds.
+    const bool cascade_ok =
+        mode == ETS_PLAN_TREE && opt.cascade_min_leaves > 0 && shape.dtype == ETS_BF16;
+    const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
+    const int64_t rows_per_item = 64;  // query rows one cascade work item handles
+    const int64_t ent_per_item = std::max<int64_t>(1, rows_per_item / G);
+    int64_t stream_total = 0, cascade_cycles = 0;
+    // cost model: one 32-token step against one block of 16 query rows
+    const int64_t step_cycles = 512;
+    for (Seg& sg : segs) {
+        sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
+                     sg.tokens > 0 &&
+                     (sg.cnt - 1) * sg.tokens * tok_bytes > sg.cnt * partial_bytes;
+        if (sg.cascade)
+            cascade_cycles += ceil_div(sg.tokens, 32) * ceil_div(sg.cnt * G, 16) * step_cycles *
+                              shape.n_kv_heads;
+        else
+            stream_total += sg.tokens * sg.cnt;
+    }
+    int64_t scap = opt.stream_chunk;
+    if (scap <= 0) {
+        scap = round_up(ceil_div(stream_total * shape.n_kv_heads, 2048), 32);
+        scap = std::min<int64_t>(std::max<int64_t>(scap, 64), 2048);
+    }
+    // time the whole call is expected to take, in clock cycles: the larger of the
+    // HBM time of the unique bytes and the matrix-core time of the cascade items
+    // spread over 1024 SIMDs; no single item should exceed half of it
+    const int64_t hbm_cycles = st.unique_kv_bytes / 2500;  // ~6 TB/s at 2.4 GHz
+    const int64_t item_budget = std::max<int64_t>(std::max(hbm_cycles, cascade_cycles / 1024) / 2,
+                                                  4 * step_cycles);
+
+    // cascade segments: chunk counts first (they fix the slot numbering)
+    std::vector<std::vector<Chunk>> seg_chunks(segs.size());
+    for (size_t s = 0; s < segs.size(); ++s) {
+        Seg& sg = segs[s];
+        sg.prefix =
+            sg.parent_seg < 0 ? 0 : segs[sg.parent_seg].prefix + segs[sg.parent_seg].n_chunks;
+        sg.n_chunks = 0;
+        if (!sg.cascade) continue;
+        int64_t ccap = opt.cascade_chunk;
+        if (ccap <= 0) {
+            const int64_t nb = ceil_div(std::min<int64_t>(sg.cnt, ent_per_item) * G, 16);
+            ccap = std::max<int64_t>(item_budget / (nb * step_cycles), 4) * 32;
+        }
+        tmp_runs.clear();
+        collect_runs(p, sg.nodes, tmp_runs);
+        cut_runs(p, tmp_runs, sg.tokens, ccap, seg_chunks[s]);
+        sg.n_chunks = (int32_t)seg_chunks[s].size();
+    }
+
+    // per leaf query: the segments of its chain that no cascade item reads are
+    // streamed by the query itself, as one run list cut into stream items
+    {
+        std::vector<int32_t> own_nodes, seg_chain;
+        int64_t slot = 0;
+        for (int32_t l = 0; l < L; ++l) {
+            const int32_t s_leaf = seg_of[p.leaf_node[l]];
+            p.part_base[l] = (int32_t)slot;
+            slot += segs[s_leaf].prefix + segs[s_leaf].n_chunks;
+            seg_chain.clear();
+            for (int32_t s = s_leaf; s >= 0; s = segs[s].parent_seg)
+                if (!segs[s].cascade) seg_chain.push_back(s);
+            own_nodes.clear();
+            for (size_t i = seg_chain.size(); i-- > 0;)
+                own_nodes.insert(own_nodes.end(), segs[seg_chain[i]].nodes.begin(),
+                                 segs[seg_chain[i]].nodes.end());
+            tmp_runs.clear();
+            collect_runs(p, own_nodes, tmp_runs);
+            int64_t tokens = 0;
+            for (const Run& r : tmp_runs) tokens += r.n;
+            cut_runs(p, tmp_runs, tokens, scap, chunks);
+            for (const Chunk& c : chunks) {
+                if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+                p.stream_items.push_back(StreamItem{l, c.run_begin, c.run_end, (int32_t)slot});
+                stream_tokens.push_back(c.tokens);
+                ++slot;
+            }
+            if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+        }
+        p.part_base[L] = (int32_t)slot;
+    }
+
+    for (size_t s = 0; s < segs.size(); ++s) {
+        const Seg& sg = segs[s];
+        for (int32_t c = 0; c < sg.n_chunks; ++c) {
+            const Chunk& ch = seg_chunks[s][c];
+            for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item) {
+                const int32_t ne = (int32_t)std::min<int64_t>(ent_per_item, sg.cnt - e0);
+                p.cascade_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
+                                                      sg.ent_begin + (int32_t)e0, ne,
+                                                      sg.prefix + c, ch.tokens, 0, 0});
+                cascade_cost.push_back((int64_t)ch.tokens * ceil_div((int64_t)ne * G, 16));
+                p.max_cascade_ent = std::max(p.max_cascade_ent, ne);
+            }
+        }
+    }
+
+    // longest items first, so that the tail of each launch is made of short ones
+    {
+        std::vector<int32_t> idx(p.stream_items.size());
+        for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
+        std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
+            return stream_tokens[a] > stream_tokens[b];
+        });
+        std::vector<StreamItem> sorted(idx.size());
+        for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.stream_items[idx[i]];
+        p.stream_items.swap(sorted);
+    }
+    {
+        std::vector<int32_t> idx(p.cascade_items.size());
+        for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
+        std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
+            return cascade_cost[a] > cascade_cost[b];
+        });
+        std::vector<CascadeItem> sorted(idx.size());
+        for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.cascade_items[idx[i]];
+        p.cascade_items.swap(sorted);
+    }
+
+    if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+    st.n_partials = p.part_base[L];
+    st.n_stream_items = (int64_t)p.stream_items.size();
+    st.n_cascade_items = (int64_t)p.cascade_items.size();
+    st.workspace_bytes = st.n_partials * shape.n_q_heads * ((int64_t)shape.head_dim + 2) * 4;
+    p.valid = true;
+    return ETS_OK;
+}
+
+}  // namespace
+
+void chain_of(const Plan& plan, int32_t leaf, std::vector<int32_t>& out) {
+    const size_t first = out.size();
+    for (int32_t x = plan.leaf_node[leaf]; x >= 0; x = plan.parent[x]) out.push_back(x);
+    std::reverse(out.begin() + (std::ptrdiff_t)first, out.end());
+}
+
+ets_status build_plan(const ets_shape& shape, const PlanOptions& opt, const ets_tree& tree,
+                      int mode, Plan& plan) {
+    plan.valid = false;
+    if (mode != ETS_PLAN_TREE && mode != ETS_PLAN_FLAT) return ETS_ERR_INVALID_ARG;
+    ets_status s = validate(tree);
+    if (s != ETS_OK) return s;
+    try {
+        return build(shape, opt, tree, mode, plan);
+    } catch (const std::bad_alloc&) {
+        plan.valid = false;
+        return ETS_ERR_NOMEM;
+    }
+}
+
+bool leaf_cover(const Plan& plan, int32_t leaf, std::vector<int64_t>& rows,
+                int32_t& n_partials) {
+    const int32_t base = plan.part_base[leaf];
+    n_partials = plan.part_base[leaf + 1] - base;
+    // run range of every slot of this leaf, taken from the work items themselves
+    std::vector<std::pair<int32_t, int32_t>> by_slot((size_t)n_partials, {-1, -1});
+    bool ok = true;
+    auto put = [&](int32_t slot, int32_t rb, int32_t re) {
+        const int32_t k = slot - base;
+        if (k < 0 || k >= n_partials || by_slot[k].first >= 0) {
+            ok = false;
+            return;
+        }
+        by_slot[k] = {rb, re};
+    };
+    for (const StreamItem& it : plan.stream_items)
+        if (it.entry == leaf) put(it.slot, it.run_begin, it.run_end);
+    for (const CascadeItem& it : plan.cascade_items)
+        for (int32_t i = 0; i < it.n_ent; ++i)
+            if (plan.ent_order[it.ent_begin + i] == leaf)
+                put(base + it.slot_off, it.run_begin, it.run_end);
+    rows.clear();
+    for (const auto& rr : by_slot) {
+        if (rr.first < 0) {
+            ok = false;
+            continue;
+        }
+        for (int32_t r = rr.first; r < rr.second; ++r)
+            for (int32_t t = 0; t < plan.runs[r].n; ++t) rows.push_back(plan.runs[r].tok + t);
+    }
+    return ok;
+}
+
+}  // namespace ets

@@ -1,0 +1,81 @@
+// Host-side planner of libetsattn: integer work on the search tree.
+//
+// Follows the tree semantics of the ETS paper (Sec. 4.1, App. B): nodes are
+// reasoning steps, a trajectory is a root->leaf chain, a non-leaf node is kept
+// iff a retained leaf lies beneath it, and ancestors' KV is shared by every
+// trajectory through them.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "etsattn.h"
+
+namespace ets {
+
+// A run of consecutive pool rows.  16 bytes, read by the kernels.
+struct Run {
+    int64_t tok;  // first pool row
+    int32_t n;    // rows
+    int32_t pad;
+};
+
+// Work item of the per-leaf streaming kernel: one leaf query reads `runs`
+// for each kv head and writes partial `slot`.
+struct StreamItem {
+    int32_t entry;      // leaf query index
+    int32_t run_begin;  // [run_begin, run_end) in Plan::runs
+    int32_t run_end;
+    int32_t slot;       // partial index (already includes part_base[entry])
+};
+
+// Work item of the shared-node kernel: the leaf queries
+// ent_order[ent_begin .. ent_begin + n_ent) all attend to `runs`; the partial
+// of entry e goes to slot part_base[e] + slot_off.
+struct CascadeItem {
+    int32_t run_begin;
+    int32_t run_end;
+    int32_t ent_begin;
+    int32_t n_ent;
+    int32_t slot_off;
+    int32_t n_tokens;
+    int32_t pad0;
+    int32_t pad1;
+};
+
+struct PlanOptions {
+    int64_t stream_chunk = 0;        // 0 = auto
+    int64_t cascade_chunk = 0;       // 0 = auto
+    int64_t cascade_min_leaves = 0;  // 0 = never use the shared-node kernel
+};
+
+struct Plan {
+    bool valid = false;
+    int mode = ETS_PLAN_TREE;
+    // copies of the caller's tree
+    std::vector<int32_t> parent, n_tokens, leaf_node;
+    std::vector<int64_t> tok_offset;
+    // derived
+    std::vector<int64_t> leaf_count;  // [N]
+    std::vector<Run> runs;
+    std::vector<StreamItem> stream_items;
+    std::vector<CascadeItem> cascade_items;
+    std::vector<int32_t> ent_order;   // leaf queries in depth-first segment order
+    std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
+    int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
+    ets_stats stats{};
+};
+
+// Builds `plan` from `tree`.  Returns ETS_OK, ETS_ERR_BAD_TREE, ETS_ERR_BAD_LEAF,
+// ETS_ERR_INVALID_ARG or ETS_ERR_NOMEM; on error plan.valid is false.
+ets_status build_plan(const ets_shape& shape, const PlanOptions& opt, const ets_tree& tree,
+                      int mode, Plan& plan);
+
+// Root->leaf chain of leaf query `leaf` (node ids), appended to `out`.
+void chain_of(const Plan& plan, int32_t leaf, std::vector<int32_t>& out);
+
+// Rows read for `leaf` according to the work items, ordered by partial slot.
+// Returns false if a slot of the leaf is produced twice or never.
+bool leaf_cover(const Plan& plan, int32_t leaf, std::vector<int64_t>& rows, int32_t& n_partials);
+
+}  // namespace ets

@@ -1,0 +1,156 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs, element by element."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_13575_amd as ets
+from workload import (CONFIGS, TreeConfig, make_tree, make_values_device, make_values_host,
+                      random_tree)
+
+from _gpu_util import (compare, gpu_attn, make_ctx, oracle_full, oracle_rows, to_device,
+                       to_host_bits)
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {
+    "tree": (ets.ETS_PLAN_TREE, {}),
+    "tree_stream_only": (ets.ETS_PLAN_TREE, {"cascade_min_leaves": 0}),
+    "flat": (ets.ETS_PLAN_FLAT, {}),
+}
+
+
+def _run_full(cfg, tree, variant, what):
+    mode, options = VARIANTS[variant]
+    k, v, q = make_values_host(cfg, tree)
+    print("case", what, variant, flush=True)
+    with make_ctx(cfg, options) as ctx:
+        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    d = cfg.head_dim
+    return compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                   oo.reshape(-1, d), ol.reshape(-1), cfg.dtype, what + "/" + variant), st
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", ["c1_tiny", "c2_w16", "c3_div", "c3_pruned"])
+def test_configs_full_parity(name, variant):
+    cfg = CONFIGS[name]
+    _run_full(cfg, make_tree(cfg), variant, name)
+
+
+@pytest.mark.parametrize("variant", ["tree", "flat"])
+def test_c4_sampled_parity(variant):
+    cfg = CONFIGS["c4_34b"]
+    tree = make_tree(cfg)
+    mode, options = VARIANTS[variant]
+    k, v, q = make_values_host(cfg, tree)
+    print("case c4", variant, flush=True)
+    with make_ctx(cfg, options) as ctx:
+        out, lse, _ = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+    r = np.random.default_rng(4)
+    leaves = r.integers(0, tree.n_leaves, size=192).astype(np.int32)
+    heads = r.integers(0, cfg.n_q_heads, size=192).astype(np.int32)
+    oo, ol = oracle_rows(cfg, tree, k, v, q, leaves, heads)
+    compare(out.cpu().numpy()[leaves, heads], lse.cpu().numpy()[leaves, heads], oo, ol,
+            cfg.dtype, "c4/" + variant)
+
+
+def test_c5_two_layers_sampled_parity():
+    """Full-size tree of the stress configuration, two of its layers, inputs drawn
+    on the device; sampled (leaf, head) rows are checked against the oracle."""
+    cfg = CONFIGS["c5_stress"]
+    tree = make_tree(cfg)
+    print("case c5 x2 layers", flush=True)
+    kd, vd, qd = make_values_device(cfg, tree, "cuda:0", layers=2)
+    r = np.random.default_rng(5)
+    with make_ctx(cfg) as ctx:
+        for layer in range(2):
+            out, lse, _ = gpu_attn(ctx, tree, kd[layer], vd[layer], qd[layer])
+            leaves = r.integers(0, tree.n_leaves, size=48).astype(np.int32)
+            heads = r.integers(0, cfg.n_q_heads, size=48).astype(np.int32)
+            k, v, q = to_host_bits(kd[layer]), to_host_bits(vd[layer]), to_host_bits(qd[layer])
+            oo, ol = oracle_rows(cfg, tree, k, v, q, leaves, heads)
+            compare(out.cpu().numpy()[leaves, heads], lse.cpu().numpy()[leaves, heads], oo, ol,
+                    cfg.dtype, "c5/layer%d" % layer)
+
+
+SHAPES = [(2, 8, 128, "bf16"), (1, 8, 64, "bf16"), (2, 2, 64, "f32"), (3, 6, 128, "f32"),
+          (4, 4, 128, "bf16"), (1, 2, 64, "bf16")]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_fuzz_irregular_forests(seed):
+    hkv, hq, d, dt = SHAPES[seed % len(SHAPES)]
+    cfg = TreeConfig("fuzz", hkv, hq, d, dt, 0, 0, 0, 0, 0, None, seed=900 + seed)
+    tree = random_tree(seed, n_nodes=50, n_leaves=21, max_tokens=90)
+    options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3]}
+    k, v, q = make_values_host(cfg, tree)
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
+        print("case fuzz", seed, mode, flush=True)
+        with make_ctx(cfg, options) as ctx:
+            out, lse, _ = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+        compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, d), ol.reshape(-1), dt, "fuzz%d/mode%d" % (seed, mode))
+
+
+def test_flat_equals_tree_and_runs_are_bitwise_reproducible():
+    cfg = CONFIGS["c3_pruned"]
+    tree = make_tree(cfg)
+    k, v, q = (to_device(x) for x in make_values_host(cfg, tree))
+    with make_ctx(cfg) as ctx:
+        o1, l1, _ = gpu_attn(ctx, tree, k, v, q, ets.ETS_PLAN_TREE)
+        o2, l2, _ = gpu_attn(ctx, tree, k, v, q, ets.ETS_PLAN_TREE)
+        of, lf, _ = gpu_attn(ctx, tree, k, v, q, ets.ETS_PLAN_FLAT)
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    assert (o1 - of).abs().max().item() <= 2e-3 and (l1 - lf).abs().max().item() <= 2e-3
+
+
+def test_edge_cases_empty_and_duplicate_leaves():
+    cfg = TreeConfig("edge", 1, 4, 128, "bf16", 0, 0, 0, 0, 0, None, seed=77)
+    parent = np.array([-1, 0, -1, 2], np.int32)
+    n_tok = np.array([0, 5, 0, 0], np.int32)
+    off = np.array([0, 0, 0, 0], np.int64)
+    leaf = np.array([1, 1, 3, 0, 1], np.int32)     # duplicates, an empty chain, a root
+    from workload import Tree
+    tree = Tree(parent, off, n_tok, leaf, 5)
+    k, v, q = make_values_host(cfg, tree)
+    q[1] = q[0]
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    with make_ctx(cfg) as ctx:
+        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q))
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "edge")
+        assert torch.equal(out[0], out[1]) and torch.equal(lse[0], lse[1])
+        assert torch.all(out[2] == 0) and torch.all(lse[2] == float("-inf"))
+        # no leaves at all: the call is a no-op
+        z32, z64 = np.zeros(0, np.int32), np.zeros(0, np.int64)
+        ctx.plan(z32, z64, z32, z32)
+        ctx.decode(None, None, 0, None, None, None, None, 0)
+
+
+def test_device_error_paths():
+    cfg = CONFIGS["c1_tiny"]
+    tree = make_tree(cfg)
+    k, v, q = (to_device(x) for x in make_values_host(cfg, tree))
+    with make_ctx(cfg) as ctx:
+        with pytest.raises(ets.EtsError) as e:
+            ctx.decode(k, v, 256, q, q, q, q, 0)
+        assert e.value.status == 6                      # no plan
+        st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        out = torch.zeros(8, 2, 64, device="cuda:0")
+        lse = torch.zeros(8, 2, device="cuda:0")
+        ws = torch.empty(st.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+        with pytest.raises(ets.EtsError) as e:
+            ctx.decode(k, v, 256, q, out, lse, ws, st.workspace_bytes - 1)
+        assert e.value.status == 5                      # workspace too small
+        with pytest.raises(ets.EtsError) as e:
+            ctx.decode(k, v, 255, q, out, lse, ws, st.workspace_bytes)
+        assert e.value.status == 2                      # node rows outside the pool
+        with pytest.raises(ets.EtsError) as e:
+            ctx.decode(k.data_ptr() + 4, v, 256, q, out, lse, ws, st.workspace_bytes)
+        assert e.value.status == 1                      # misaligned pool
+        assert torch.all(out == 0) and torch.all(lse == 0)   # outputs untouched on error

@@ -1,0 +1,180 @@
+"""Host logic of libetsattn, no GPU needed: the library loads and exports what
+the header declares; the planner's indexing equals the oracle's walk bit for
+bit; the work items tile every leaf's chain exactly once; every error path
+reports its status code."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2502_13575_amd as ets
+from workload import CONFIGS, make_tree, random_tree
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _ctx(cfg_or_shape, device=-1):
+    if isinstance(cfg_or_shape, tuple):
+        hkv, hq, d, dt = cfg_or_shape
+    else:
+        c = cfg_or_shape
+        hkv, hq, d = c.n_kv_heads, c.n_q_heads, c.head_dim
+        dt = ets.ETS_F32 if c.dtype == "f32" else ets.ETS_BF16
+    return ets.Context(hkv, hq, d, dt, device)
+
+
+def _chain_rows(t, optr, onodes, l):
+    nodes = onodes[optr[l]:optr[l + 1]]
+    if len(nodes) == 0:
+        return np.zeros(0, dtype=np.int64)
+    return np.concatenate([np.arange(t.tok_offset[n], t.tok_offset[n] + t.n_tokens[n])
+                           for n in nodes]).astype(np.int64)
+
+
+def _check_plan_against_oracle(ctx, t, mode, leaves=None):
+    st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, mode)
+    ost = oracle.tree_stats(t.parent, t.n_tokens, t.leaf_node)
+    assert st.unique_tokens == ost["unique_tokens"]
+    assert st.flat_tokens == ost["flat_tokens"]
+    assert st.live_nodes == ost["live_nodes"]
+    assert np.array_equal(ctx.leaf_counts(), ost["leaf_count"])
+    optr, onodes = oracle.paths(t.parent, t.leaf_node)
+    ptr, nodes = ctx.paths()
+    assert np.array_equal(ptr, optr) and np.array_equal(nodes, onodes)
+    total_partials = 0
+    for l in (range(t.n_leaves) if leaves is None else leaves):
+        rows, npart = ctx.leaf_cover(l)
+        want = _chain_rows(t, optr, onodes, l)
+        assert np.array_equal(np.sort(rows), np.sort(want)), (mode, l)
+        total_partials += npart
+    if leaves is None:
+        assert total_partials == st.n_partials
+    esz = 4 if ctx.shape.dtype == ets.ETS_F32 else 2
+    assert st.unique_kv_bytes == st.unique_tokens * 2 * ctx.shape.n_kv_heads * ctx.shape.head_dim * esz
+    assert st.workspace_bytes == st.n_partials * ctx.shape.n_q_heads * (ctx.shape.head_dim + 2) * 4
+    return st
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "etsattn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ets_[a-z_]+)\s*\(", hdr)))
+    assert "ets_tree_decode_attn" in names and "ets_plan" in names and len(names) >= 10
+    lib = C.CDLL(ets.library_path())
+    for n in names:
+        assert hasattr(lib, n), "missing export: " + n
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+@pytest.mark.parametrize("mode", [ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT])
+def test_plan_indexing_matches_oracle_on_configs(name, mode):
+    cfg = CONFIGS[name]
+    t = make_tree(cfg)
+    with _ctx(cfg) as ctx:
+        ctx.set_option("cascade_min_leaves", 2)
+        leaves = None if t.n_leaves <= 64 else list(range(0, t.n_leaves, t.n_leaves // 32))
+        st = _check_plan_against_oracle(ctx, t, mode, leaves)
+        if mode == ets.ETS_PLAN_FLAT:
+            assert st.n_cascade_items == 0
+        elif cfg.dtype == "bf16":
+            assert st.n_cascade_items > 0
+
+
+def test_c1_closed_form_counts():
+    cfg = CONFIGS["c1_tiny"]
+    t = make_tree(cfg)
+    with _ctx(cfg) as ctx:
+        st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert (st.n_nodes, st.live_nodes, st.n_leaves) == (15, 15, 8)
+        assert (st.unique_tokens, st.flat_tokens) == (256, 640)
+        assert st.n_segments == 15 and st.min_pool_tokens == 256
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plan_fuzz_irregular_forests(seed):
+    t = random_tree(seed, n_nodes=60, n_leaves=25, max_tokens=70)
+    shapes = [(2, 8, 128, ets.ETS_BF16), (1, 8, 64, ets.ETS_BF16), (2, 2, 64, ets.ETS_F32)]
+    with _ctx(shapes[seed % 3]) as ctx:
+        ctx.set_option("cascade_min_leaves", 2)
+        ctx.set_option("stream_chunk", [0, 32, 64][seed % 3])
+        ctx.set_option("cascade_chunk", [0, 32, 96][(seed // 3) % 3])
+        for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
+            _check_plan_against_oracle(ctx, t, mode)
+
+
+def test_chain_compaction_merges_single_child_chains():
+    # root(4) - a(3) - b(5) with two leaves under b: one segment for root,a,b + 2 leaf segments
+    parent = np.array([-1, 0, 1, 2, 2], np.int32)
+    n_tok = np.array([4, 3, 5, 2, 6], np.int32)
+    off = np.array([0, 4, 7, 12, 14], np.int64)
+    with _ctx((1, 4, 128, ets.ETS_BF16)) as ctx:
+        st = ctx.plan(parent, off, n_tok, np.array([3, 4], np.int32))
+        assert st.n_segments == 3 and st.live_nodes == 5
+        assert st.unique_tokens == 20 and st.flat_tokens == 12 * 2 + 8
+
+
+def test_empty_tree_and_empty_chains():
+    with _ctx((1, 1, 64, ets.ETS_F32)) as ctx:
+        z32, z64 = np.zeros(0, np.int32), np.zeros(0, np.int64)
+        st = ctx.plan(z32, z64, z32, z32)
+        assert st.n_leaves == 0 and st.n_partials == 0 and st.workspace_bytes == 0
+        st = ctx.plan(np.array([-1], np.int32), np.array([0], np.int64), np.array([0], np.int32),
+                      np.array([0, 0], np.int32))
+        assert st.n_leaves == 2 and st.n_partials == 0 and st.unique_tokens == 0
+        rows, npart = ctx.leaf_cover(1)
+        assert rows.size == 0 and npart == 0
+
+
+def _status(fn):
+    with pytest.raises(ets.EtsError) as e:
+        fn()
+    return e.value.status
+
+
+def test_error_paths():
+    assert _status(lambda: ets.Context(8, 32, 96, ets.ETS_BF16, -1)) == 4      # head_dim
+    assert _status(lambda: ets.Context(8, 30, 128, ets.ETS_BF16, -1)) == 4     # Hq % Hkv
+    assert _status(lambda: ets.Context(2, 32, 128, ets.ETS_BF16, -1)) == 4     # G = 16
+    assert _status(lambda: ets.Context(8, 32, 128, 7, -1)) == 4                # dtype
+    t = make_tree(CONFIGS["c1_tiny"])
+    with _ctx(CONFIGS["c1_tiny"]) as ctx:
+        assert _status(ctx.stats) == 6                                          # no plan yet
+        bad = t.parent.copy(); bad[4] = 4
+        assert _status(lambda: ctx.plan(bad, t.tok_offset, t.n_tokens, t.leaf_node)) == 2
+        bad = t.parent.copy(); bad[2] = 9
+        assert _status(lambda: ctx.plan(bad, t.tok_offset, t.n_tokens, t.leaf_node)) == 2
+        bad = t.parent.copy(); bad[0] = -2
+        assert _status(lambda: ctx.plan(bad, t.tok_offset, t.n_tokens, t.leaf_node)) == 2
+        nt = t.n_tokens.copy(); nt[3] = -1
+        assert _status(lambda: ctx.plan(t.parent, t.tok_offset, nt, t.leaf_node)) == 2
+        lf = t.leaf_node.copy(); lf[1] = 15
+        assert _status(lambda: ctx.plan(t.parent, t.tok_offset, t.n_tokens, lf)) == 3
+        assert _status(ctx.stats) == 6                                          # failed plan dropped
+        assert _status(lambda: ctx.set_option("no_such_knob", 1)) == 1
+        assert _status(lambda: ctx.set_option("stream_chunk", -5)) == 1
+        ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert _status(lambda: ctx.leaf_cover(8)) == 3
+        # a host-only context cannot launch
+        assert _status(lambda: ctx.decode(16, 16, 256, 16, 16, 16, 16, 1 << 20)) == 7
+    lib = ets.load_library()
+    assert lib.ets_create(None, None, -1) == 1
+    assert lib.ets_plan(None, None, 0) == 1
+    assert lib.ets_plan_stats(None, None) == 1
+    assert lib.ets_tree_decode_attn(None, None, None, 0, None, None, None, None, 0, None) == 1
+    lib.ets_destroy(None)
+    assert ets.ets_strerror(0) == "ok" and "tree" in ets.ets_strerror(2)
+
+
+def test_sharing_reduces_partials_and_flat_is_per_leaf():
+    cfg = CONFIGS["c3_pruned"]
+    t = make_tree(cfg)
+    with _ctx(cfg) as ctx:
+        ctx.set_option("cascade_min_leaves", 2)
+        tree = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, ets.ETS_PLAN_TREE).as_dict()
+        flat = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, ets.ETS_PLAN_FLAT).as_dict()
+    assert tree["unique_tokens"] == flat["unique_tokens"]
+    assert flat["n_cascade_items"] == 0 and flat["n_stream_items"] >= t.n_leaves
+    assert tree["n_cascade_items"] > 0
