@@ -105,6 +105,8 @@ typedef struct {
     int64_t n_cascade_items; /* work items of the shared-node kernel                     */
     int64_t min_pool_tokens; /* pools must hold at least this many rows                  */
     int64_t workspace_bytes; /* device scratch ets_tree_decode_attn needs                */
+    int64_t cascade_tokens;  /* unique tokens read (once) by the shared-node kernel      */
+    int64_t stream_tokens;   /* tokens read by the streaming kernel, repeats included    */
 } ets_stats;
 
 typedef enum {
@@ -156,6 +158,7 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
  *                    read once by the shared-node kernel; below it every leaf
  *                    streams the segment itself (default 2; 0 disables the
  *                    shared-node kernel)
+ *   "profile"        1 = record kernel times (see ets_profile_read), 0 = off
  * Unknown key or negative value: ETS_ERR_INVALID_ARG. */
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 
@@ -176,6 +179,19 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
                                 int64_t pool_tokens, const void* q, float* out, float* lse,
                                 void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* Kernel times for benchmarks.  After ets_set_option(ctx, "profile", 1) every
+ * ets_tree_decode_attn call brackets its kernels with HIP events on the call's
+ * stream (this mode may create events, i.e. allocate; at most 8192 calls are
+ * kept between reads).  ets_profile_read waits for the last recorded call,
+ * returns the summed kernel times since the previous read and clears them. */
+typedef struct {
+    int64_t calls;
+    double stream_ms;  /* per-leaf streaming kernel  */
+    double cascade_ms; /* shared-node kernel         */
+    double merge_ms;   /* log-sum-exp merge kernel   */
+} ets_profile;
+ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out /* host */);
 
 /* Static string for a status code. */
 const char* ets_strerror(int status);

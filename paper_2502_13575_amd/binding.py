@@ -37,10 +37,15 @@ class EtsStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "n_nodes", "live_nodes", "n_leaves", "unique_tokens", "flat_tokens", "unique_kv_bytes",
         "flat_kv_bytes", "n_segments", "n_partials", "n_stream_items", "n_cascade_items",
-        "min_pool_tokens", "workspace_bytes")]
+        "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class EtsProfile(C.Structure):
+    _fields_ = [("calls", C.c_int64), ("stream_ms", C.c_double), ("cascade_ms", C.c_double),
+                ("merge_ms", C.c_double)]
 
 
 def library_path() -> str:
@@ -77,6 +82,8 @@ def load_library():
     lib.ets_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
     lib.ets_tree_decode_attn.restype = C.c_int
     lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
+    lib.ets_profile_read.restype = C.c_int
+    lib.ets_profile_read.argtypes = [vp, C.POINTER(EtsProfile)]
     lib.ets_strerror.restype = C.c_char_p
     lib.ets_strerror.argtypes = [C.c_int]
     _lib = lib
@@ -183,6 +190,12 @@ def ets_tree_decode_attn(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse, wor
         "ets_tree_decode_attn")
 
 
+def ets_profile_read(ctx) -> EtsProfile:
+    pr = EtsProfile()
+    _check(load_library().ets_profile_read(ctx, C.byref(pr)), "ets_profile_read")
+    return pr
+
+
 class Context:
     """Owns one ets_ctx.  Thin convenience over the functions above."""
 
@@ -226,6 +239,9 @@ class Context:
 
     def leaf_cover(self, leaf):
         return ets_plan_leaf_cover(self._ctx, leaf)
+
+    def profile_read(self) -> EtsProfile:
+        return ets_profile_read(self._ctx)
 
     def decode(self, k_pool, v_pool, pool_tokens, q, out, lse, workspace, workspace_bytes,
                hip_stream=None):

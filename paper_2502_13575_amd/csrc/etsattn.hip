@@ -6,6 +6,7 @@
 #include <new>
 #include <vector>
 
+#include "cascade_kernel.hpp"
 #include "etsattn.h"
 #include "merge_kernel.hpp"
 #include "plan.h"
@@ -29,6 +30,10 @@ struct ets_ctx {
     int32_t* d_part_base = nullptr;
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
+    // kernel timing (benchmarks only): four events per recorded call
+    bool profile = false;
+    std::vector<hipEvent_t> events;
+    size_t calls_recorded = 0;
 };
 
 namespace {
@@ -144,8 +149,42 @@ void launch_stream_g(const ets_ctx* c, const LaunchArgs& a) {
     }
 }
 
-void launch_all(const ets_ctx* c, const LaunchArgs& a) {
+template <int NB>
+void launch_cascade_class(const ets_ctx* c, const LaunchArgs& a, int cls) {
+    const int32_t first = c->plan.cascade_class_begin[cls];
+    const int64_t n_items = c->plan.cascade_class_begin[cls + 1] - first;
+    if (n_items <= 0) return;
+    const int g = c->shape.n_q_heads / c->shape.n_kv_heads;
+    const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
+    const unsigned grid = (unsigned)(n_items * c->shape.n_kv_heads);
+    hipLaunchKernelGGL((cascade_attn_kernel<NB>), dim3(grid), dim3(64), 0, a.stream,
+                       static_cast<const bf16_t*>(a.k), static_cast<const bf16_t*>(a.v),
+                       static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade + first,
+                       c->d_ent_order, c->d_part_base, c->shape.n_kv_heads, g_shift,
+                       c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+}
+
+constexpr size_t kMaxProfiledCalls = 8192;
+
+// Event `which` (0..3) of the call being recorded, created on first use.
+void mark(ets_ctx* c, int which, hipStream_t stream) {
+    if (!c->profile || c->calls_recorded >= kMaxProfiledCalls) return;
+    const size_t idx = c->calls_recorded * 4 + (size_t)which;
+    while (c->events.size() <= idx) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) {
+            (void)hipGetLastError();
+            c->profile = false;
+            return;
+        }
+        c->events.push_back(e);
+    }
+    (void)hipEventRecord(c->events[idx], stream);
+}
+
+void launch_all(ets_ctx* c, const LaunchArgs& a) {
     const bool bf = c->shape.dtype == ETS_BF16;
+    mark(c, 0, a.stream);
     if (c->shape.head_dim == 128) {
         if (bf) launch_stream_g<bf16_t, 128>(c, a);
         else launch_stream_g<float, 128>(c, a);
@@ -153,8 +192,12 @@ void launch_all(const ets_ctx* c, const LaunchArgs& a) {
         if (bf) launch_stream_g<bf16_t, 64>(c, a);
         else launch_stream_g<float, 64>(c, a);
     }
+    mark(c, 1, a.stream);
+    launch_cascade_class<4>(c, a, 2);  // heaviest items first
+    launch_cascade_class<2>(c, a, 1);
+    launch_cascade_class<1>(c, a, 0);
+    mark(c, 2, a.stream);
     const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
-    if (pairs == 0) return;
     const unsigned grid = (unsigned)((pairs + 3) / 4);
     if (c->shape.head_dim == 128)
         hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, a.stream,
@@ -164,6 +207,8 @@ void launch_all(const ets_ctx* c, const LaunchArgs& a) {
         hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, (int)c->plan.stats.n_leaves, c->shape.n_q_heads,
                            a.ws_o, a.ws_ml, a.out, a.lse);
+    mark(c, 3, a.stream);
+    if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
 }
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -201,6 +246,10 @@ void ets_destroy(ets_ctx* ctx) {
             (void)hipFree(ctx->d_buf);
         }
     }
+    if (!ctx->events.empty()) {
+        DeviceGuard guard(ctx->device);
+        for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+    }
     delete ctx;
 }
 
@@ -209,6 +258,10 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
     if (!std::strcmp(key, "stream_chunk")) ctx->opt.stream_chunk = value;
     else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
     else if (!std::strcmp(key, "cascade_min_leaves")) ctx->opt.cascade_min_leaves = value;
+    else if (!std::strcmp(key, "profile")) {
+        if (value != 0 && ctx->device < 0) return ETS_ERR_HIP;
+        ctx->profile = value != 0;
+    }
     else return ETS_ERR_INVALID_ARG;
     return ETS_OK;
 }
@@ -300,7 +353,6 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
         misaligned(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
         return ETS_ERR_INVALID_ARG;
 
-    if (!ctx->plan.cascade_items.empty()) return ETS_ERR_UNSUPPORTED;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return ETS_ERR_HIP;
     LaunchArgs a;
@@ -318,6 +370,32 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
     ctx->last_stream = a.stream;
     ctx->stream_used = true;
     if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    return ETS_OK;
+}
+
+ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out) {
+    if (!ctx || !out) return ETS_ERR_INVALID_ARG;
+    *out = ets_profile{};
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    if (ctx->calls_recorded == 0) return ETS_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    const size_t n = ctx->calls_recorded;
+    ctx->calls_recorded = 0;
+    if (hipEventSynchronize(ctx->events[n * 4 - 1]) != hipSuccess) return ETS_ERR_HIP;
+    for (size_t i = 0; i < n; ++i) {
+        float ms[3] = {0.f, 0.f, 0.f};
+        for (int k = 0; k < 3; ++k)
+            if (hipEventElapsedTime(&ms[k], ctx->events[i * 4 + k], ctx->events[i * 4 + k + 1]) !=
+                hipSuccess) {
+                (void)hipGetLastError();
+                return ETS_ERR_HIP;
+            }
+        out->stream_ms += ms[0];
+        out->cascade_ms += ms[1];
+        out->merge_ms += ms[2];
+    }
+    out->calls = (int64_t)n;
     return ETS_OK;
 }
 

@@ -196,7 +196,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // to the shared-node kernel when the KV bytes it saves exceed the partial
     // bytes it adds.
     const bool cascade_ok =
-        mode == ETS_PLAN_TREE && opt.cascade_min_leaves > 0 && shape.dtype == ETS_BF16;
+        mode == ETS_PLAN_TREE && opt.cascade_min_leaves > 0 && shape.dtype == ETS_BF16 &&
+        shape.head_dim == 128;  // what the shared-node kernel is built for
     const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
     const int64_t rows_per_item = 64;  // query rows one cascade work item handles
     const int64_t ent_per_item = std::max<int64_t>(1, rows_per_item / G);
@@ -207,6 +208,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
                      sg.tokens > 0 &&
                      (sg.cnt - 1) * sg.tokens * tok_bytes > sg.cnt * partial_bytes;
+        if (sg.cascade) st.cascade_tokens += sg.tokens;
+        else st.stream_tokens += sg.tokens * sg.cnt;
         if (sg.cascade)
             cascade_cycles += ceil_div(sg.tokens, 32) * ceil_div(sg.cnt * G, 16) * step_cycles *
                               shape.n_kv_heads;
@@ -303,14 +306,23 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         p.stream_items.swap(sorted);
     }
     {
+        auto cls = [&](const CascadeItem& it) {
+            const int64_t nb = ceil_div((int64_t)it.n_ent * G, 16);
+            return nb <= 1 ? 0 : nb == 2 ? 1 : 2;
+        };
         std::vector<int32_t> idx(p.cascade_items.size());
         for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
         std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
+            const int ca = cls(p.cascade_items[a]), cb = cls(p.cascade_items[b]);
+            if (ca != cb) return ca < cb;
             return cascade_cost[a] > cascade_cost[b];
         });
         std::vector<CascadeItem> sorted(idx.size());
         for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.cascade_items[idx[i]];
         p.cascade_items.swap(sorted);
+        for (int c = 0; c < 4; ++c) p.cascade_class_begin[c] = 0;
+        for (const CascadeItem& it : p.cascade_items)
+            for (int c = cls(it) + 1; c < 4; ++c) p.cascade_class_begin[c] += 1;
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;

@@ -46,7 +46,7 @@ struct CascadeItem {
 struct PlanOptions {
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
-    int64_t cascade_min_leaves = 0;  // 0 = never use the shared-node kernel
+    int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
 };
 
 struct Plan {
@@ -63,6 +63,9 @@ struct Plan {
     std::vector<int32_t> ent_order;   // leaf queries in depth-first segment order
     std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
+    // cascade_items is ordered by the number of 16-row blocks an item needs:
+    // class 0 = one block, class 1 = two, class 2 = three or four
+    int32_t cascade_class_begin[4] = {0, 0, 0, 0};
     ets_stats stats{};
 };
 

@@ -38,7 +38,11 @@ def _run_full(cfg, tree, variant, what):
 @pytest.mark.parametrize("name", ["c1_tiny", "c2_w16", "c3_div", "c3_pruned"])
 def test_configs_full_parity(name, variant):
     cfg = CONFIGS[name]
-    _run_full(cfg, make_tree(cfg), variant, name)
+    _, st = _run_full(cfg, make_tree(cfg), variant, name)
+    if variant == "tree" and cfg.dtype == "bf16":
+        assert st.n_cascade_items > 0 and st.cascade_tokens > 0     # the MFMA path ran
+    if variant != "tree":
+        assert st.n_cascade_items == 0
 
 
 @pytest.mark.parametrize("variant", ["tree", "flat"])
