@@ -6,11 +6,11 @@
 #include <new>
 #include <vector>
 
-#include "cascade_kernel.hpp"
 #include "etsattn.h"
 #include "merge_kernel.hpp"
 #include "plan.h"
 #include "stream_kernel.hpp"
+#include "tree_attn_kernel.hpp"
 
 using namespace ets;
 
@@ -149,18 +149,16 @@ void launch_stream_g(const ets_ctx* c, const LaunchArgs& a) {
     }
 }
 
-template <int NB>
-void launch_cascade_class(const ets_ctx* c, const LaunchArgs& a, int cls) {
-    const int32_t first = c->plan.cascade_class_begin[cls];
-    const int64_t n_items = c->plan.cascade_class_begin[cls + 1] - first;
+void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
+    const int64_t n_items = (int64_t)c->plan.cascade_items.size();
     if (n_items <= 0) return;
     const int g = c->shape.n_q_heads / c->shape.n_kv_heads;
     const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
     const unsigned grid = (unsigned)(n_items * c->shape.n_kv_heads);
-    hipLaunchKernelGGL((cascade_attn_kernel<NB>), dim3(grid), dim3(64), 0, a.stream,
+    hipLaunchKernelGGL(tree_attn_kernel, dim3(grid), dim3(256), 0, a.stream,
                        static_cast<const bf16_t*>(a.k), static_cast<const bf16_t*>(a.v),
-                       static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade + first,
-                       c->d_ent_order, c->d_part_base, c->shape.n_kv_heads, g_shift,
+                       static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_ent_order,
+                       c->d_part_base, c->shape.n_kv_heads, g_shift,
                        c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
 }
 
@@ -193,9 +191,7 @@ void launch_all(ets_ctx* c, const LaunchArgs& a) {
         else launch_stream_g<float, 64>(c, a);
     }
     mark(c, 1, a.stream);
-    launch_cascade_class<4>(c, a, 2);  // heaviest items first
-    launch_cascade_class<2>(c, a, 1);
-    launch_cascade_class<1>(c, a, 0);
+    launch_tree_attn(c, a);
     mark(c, 2, a.stream);
     const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
     const unsigned grid = (unsigned)((pairs + 3) / 4);
@@ -258,6 +254,10 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
     if (!std::strcmp(key, "stream_chunk")) ctx->opt.stream_chunk = value;
     else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
     else if (!std::strcmp(key, "cascade_min_leaves")) ctx->opt.cascade_min_leaves = value;
+    else if (!std::strcmp(key, "cascade_rows")) {
+        if (value != 32 && value != 64 && value != 128) return ETS_ERR_INVALID_ARG;
+        ctx->opt.cascade_rows = value;
+    } else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
     else if (!std::strcmp(key, "profile")) {
         if (value != 0 && ctx->device < 0) return ETS_ERR_HIP;
         ctx->profile = value != 0;

@@ -49,9 +49,11 @@ void collect_runs(const Plan& p, const std::vector<int32_t>& nodes, std::vector<
     }
 }
 
-// Cuts `src` (total `tokens` rows) into pieces of at most `cap` rows, sized
-// evenly in multiples of 32 rows, appending the pieces' runs to plan.runs.
-void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
+// Cuts `src` (total `tokens` rows) into chunks of at most `cap` rows, sized
+// evenly in multiples of 32 rows, appending the chunks' runs to plan.runs.  With
+// piece > 0 no emitted run is longer than `piece` rows (the matrix-core kernel
+// walks its run list in steps of at most 32 rows).
+void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap, int64_t piece,
               std::vector<Chunk>& chunks) {
     chunks.clear();
     if (tokens <= 0) return;
@@ -66,7 +68,8 @@ void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
         Chunk c{(int32_t)p.runs.size(), 0, (int32_t)want};
         while (want > 0) {
             const int64_t avail = src[ri].n - used;
-            const int64_t take = std::min(avail, want);
+            int64_t take = std::min(avail, want);
+            if (piece > 0) take = std::min(take, piece);
             p.runs.push_back(Run{src[ri].tok + used, (int32_t)take, 0});
             used += take;
             want -= take;
@@ -189,46 +192,58 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         }
     }
 
-    // Which kernel reads which segment.  The shared-node kernel reads a segment
-    // once for all `cnt` leaf queries beneath it but costs one partial result per
-    // query and query head (written, then read by the merge); otherwise every
-    // query streams the segment itself as part of its own item.  A segment goes
-    // to the shared-node kernel when the KV bytes it saves exceed the partial
-    // bytes it adds.
-    const bool cascade_ok =
-        mode == ETS_PLAN_TREE && opt.cascade_min_leaves > 0 && shape.dtype == ETS_BF16 &&
-        shape.head_dim == 128;  // what the shared-node kernel is built for
+    // Which kernel reads which segment.  The matrix-core kernel reads a shared
+    // segment once for all `cnt` leaf queries beneath it but costs one partial
+    // result per query and query head (written, then read by the merge); otherwise
+    // every query reads the segment itself as part of its own item.  A segment is
+    // shared when the KV bytes this saves exceed the partial bytes it adds.
+    const bool use_mfma = opt.mfma != 0 && shape.dtype == ETS_BF16 && shape.head_dim == 128;
+    const bool cascade_ok = mode == ETS_PLAN_TREE && use_mfma && opt.cascade_min_leaves > 0;
+    const int64_t piece = use_mfma ? 32 : 0;
     const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
-    const int64_t rows_per_item = 64;  // query rows one cascade work item handles
-    const int64_t ent_per_item = std::max<int64_t>(1, rows_per_item / G);
-    int64_t stream_total = 0, cascade_cycles = 0;
-    // cost model: one 32-token step against one block of 16 query rows
-    const int64_t step_cycles = 512;
+    const int64_t ent_per_item = std::max<int64_t>(1, opt.cascade_rows / G);
+    // cost model in nanoseconds per tile of 128 tokens: a workgroup that is
+    // waiting on memory needs about t_mem per tile; one that computes needs
+    // t_blk per 32-token step and 16-row block of its busiest wave
+    const int64_t t_mem = 1200, t_blk = 220;
+    auto tile_cost = [&](int64_t rows) {
+        if (rows <= 32) return t_mem;
+        const int64_t blocks_per_wave = std::min<int64_t>(2, ceil_div(ceil_div(rows, 16), 4));
+        return std::max(t_mem, 4 * blocks_per_wave * t_blk);
+    };
+    int64_t own_total = 0, work_ns = 0;
     for (Seg& sg : segs) {
         sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
                      sg.tokens > 0 &&
                      (sg.cnt - 1) * sg.tokens * tok_bytes > sg.cnt * partial_bytes;
-        if (sg.cascade) st.cascade_tokens += sg.tokens;
-        else st.stream_tokens += sg.tokens * sg.cnt;
-        if (sg.cascade)
-            cascade_cycles += ceil_div(sg.tokens, 32) * ceil_div(sg.cnt * G, 16) * step_cycles *
-                              shape.n_kv_heads;
-        else
-            stream_total += sg.tokens * sg.cnt;
+        if (sg.cascade) {
+            st.cascade_tokens += sg.tokens;
+            for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item)
+                work_ns += ceil_div(sg.tokens, 128) *
+                           tile_cost(std::min(ent_per_item, sg.cnt - e0) * G) * shape.n_kv_heads;
+        } else {
+            st.stream_tokens += sg.tokens * sg.cnt;
+            own_total += sg.tokens * sg.cnt;
+            work_ns += ceil_div(sg.tokens, 128) * t_mem * sg.cnt * shape.n_kv_heads;
+        }
     }
+    // time the whole call is expected to take: the larger of the HBM time of the
+    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 256 compute
+    // units; no single item should take more than a third of it
+    const int64_t hbm_ns = st.unique_kv_bytes / 5500;
+    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 256) / 3, 4 * t_mem);
+
     int64_t scap = opt.stream_chunk;
     if (scap <= 0) {
-        scap = round_up(ceil_div(stream_total * shape.n_kv_heads, 2048), 32);
-        scap = std::min<int64_t>(std::max<int64_t>(scap, 64), 2048);
+        if (use_mfma) {
+            scap = item_budget_ns / t_mem * 128;
+        } else {
+            scap = round_up(ceil_div(own_total * shape.n_kv_heads, 2048), 32);
+            scap = std::min<int64_t>(std::max<int64_t>(scap, 64), 2048);
+        }
     }
-    // time the whole call is expected to take, in clock cycles: the larger of the
-    // HBM time of the unique bytes and the matrix-core time of the cascade items
-    // spread over 1024 SIMDs; no single item should exceed half of it
-    const int64_t hbm_cycles = st.unique_kv_bytes / 2500;  // ~6 TB/s at 2.4 GHz
-    const int64_t item_budget = std::max<int64_t>(std::max(hbm_cycles, cascade_cycles / 1024) / 2,
-                                                  4 * step_cycles);
 
-    // cascade segments: chunk counts first (they fix the slot numbering)
+    // shared segments: chunk counts first (they fix the slot numbering)
     std::vector<std::vector<Chunk>> seg_chunks(segs.size());
     for (size_t s = 0; s < segs.size(); ++s) {
         Seg& sg = segs[s];
@@ -237,25 +252,26 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         sg.n_chunks = 0;
         if (!sg.cascade) continue;
         int64_t ccap = opt.cascade_chunk;
-        if (ccap <= 0) {
-            const int64_t nb = ceil_div(std::min<int64_t>(sg.cnt, ent_per_item) * G, 16);
-            ccap = std::max<int64_t>(item_budget / (nb * step_cycles), 4) * 32;
-        }
+        if (ccap <= 0)
+            ccap = item_budget_ns / tile_cost(std::min(ent_per_item, sg.cnt) * G) * 128;
         tmp_runs.clear();
         collect_runs(p, sg.nodes, tmp_runs);
-        cut_runs(p, tmp_runs, sg.tokens, ccap, seg_chunks[s]);
+        cut_runs(p, tmp_runs, sg.tokens, ccap, piece, seg_chunks[s]);
         sg.n_chunks = (int32_t)seg_chunks[s].size();
     }
 
-    // per leaf query: the segments of its chain that no cascade item reads are
-    // streamed by the query itself, as one run list cut into stream items
+    // per leaf query: the segments of its chain that no shared item reads are read
+    // by the query itself, as one run list cut into items
+    std::vector<int32_t> ent_pos(L, 0);
+    for (int32_t i = 0; i < L; ++i) ent_pos[p.ent_order[i]] = i;
     {
         std::vector<int32_t> own_nodes, seg_chain;
         int64_t slot = 0;
         for (int32_t l = 0; l < L; ++l) {
             const int32_t s_leaf = seg_of[p.leaf_node[l]];
             p.part_base[l] = (int32_t)slot;
-            slot += segs[s_leaf].prefix + segs[s_leaf].n_chunks;
+            const int32_t shared_slots = segs[s_leaf].prefix + segs[s_leaf].n_chunks;
+            slot += shared_slots;
             seg_chain.clear();
             for (int32_t s = s_leaf; s >= 0; s = segs[s].parent_seg)
                 if (!segs[s].cascade) seg_chain.push_back(s);
@@ -267,11 +283,21 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
             collect_runs(p, own_nodes, tmp_runs);
             int64_t tokens = 0;
             for (const Run& r : tmp_runs) tokens += r.n;
-            cut_runs(p, tmp_runs, tokens, scap, chunks);
+            cut_runs(p, tmp_runs, tokens, scap, piece, chunks);
+            int32_t c_idx = 0;
             for (const Chunk& c : chunks) {
                 if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
-                p.stream_items.push_back(StreamItem{l, c.run_begin, c.run_end, (int32_t)slot});
-                stream_tokens.push_back(c.tokens);
+                if (use_mfma) {
+                    p.cascade_items.push_back(CascadeItem{c.run_begin, c.run_end, ent_pos[l], 1,
+                                                          shared_slots + c_idx, c.tokens, 0, 0});
+                    cascade_cost.push_back(ceil_div(c.tokens, 128) * t_mem);
+                    p.max_cascade_ent = std::max(p.max_cascade_ent, 1);
+                } else {
+                    p.stream_items.push_back(
+                        StreamItem{l, c.run_begin, c.run_end, (int32_t)slot});
+                    stream_tokens.push_back(c.tokens);
+                }
+                ++c_idx;
                 ++slot;
             }
             if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
@@ -288,7 +314,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 p.cascade_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
                                                       sg.ent_begin + (int32_t)e0, ne,
                                                       sg.prefix + c, ch.tokens, 0, 0});
-                cascade_cost.push_back((int64_t)ch.tokens * ceil_div((int64_t)ne * G, 16));
+                cascade_cost.push_back(ceil_div(ch.tokens, 128) * tile_cost((int64_t)ne * G));
                 p.max_cascade_ent = std::max(p.max_cascade_ent, ne);
             }
         }
@@ -306,23 +332,14 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         p.stream_items.swap(sorted);
     }
     {
-        auto cls = [&](const CascadeItem& it) {
-            const int64_t nb = ceil_div((int64_t)it.n_ent * G, 16);
-            return nb <= 1 ? 0 : nb == 2 ? 1 : 2;
-        };
         std::vector<int32_t> idx(p.cascade_items.size());
         for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
         std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
-            const int ca = cls(p.cascade_items[a]), cb = cls(p.cascade_items[b]);
-            if (ca != cb) return ca < cb;
             return cascade_cost[a] > cascade_cost[b];
         });
         std::vector<CascadeItem> sorted(idx.size());
         for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.cascade_items[idx[i]];
         p.cascade_items.swap(sorted);
-        for (int c = 0; c < 4; ++c) p.cascade_class_begin[c] = 0;
-        for (const CascadeItem& it : p.cascade_items)
-            for (int c = cls(it) + 1; c < 4; ++c) p.cascade_class_begin[c] += 1;
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;

@@ -29,9 +29,9 @@ struct StreamItem {
     int32_t slot;       // partial index (already includes part_base[entry])
 };
 
-// Work item of the shared-node kernel: the leaf queries
-// ent_order[ent_begin .. ent_begin + n_ent) all attend to `runs`; the partial
-// of entry e goes to slot part_base[e] + slot_off.
+// Work item of the matrix-core kernel: the leaf queries
+// ent_order[ent_begin .. ent_begin + n_ent) all attend to `runs` (each run at
+// most 32 rows); the partial of entry e goes to slot part_base[e] + slot_off.
 struct CascadeItem {
     int32_t run_begin;
     int32_t run_end;
@@ -46,6 +46,8 @@ struct CascadeItem {
 struct PlanOptions {
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
+    int64_t cascade_rows = 128;      // query rows per shared work item (32, 64 or 128)
+    int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
 };
 
@@ -63,9 +65,6 @@ struct Plan {
     std::vector<int32_t> ent_order;   // leaf queries in depth-first segment order
     std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
-    // cascade_items is ordered by the number of 16-row blocks an item needs:
-    // class 0 = one block, class 1 = two, class 2 = three or four
-    int32_t cascade_class_begin[4] = {0, 0, 0, 0};
     ets_stats stats{};
 };
 

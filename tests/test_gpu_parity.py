@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 
 VARIANTS = {
     "tree": (ets.ETS_PLAN_TREE, {}),
-    "tree_stream_only": (ets.ETS_PLAN_TREE, {"cascade_min_leaves": 0}),
+    "tree_no_sharing": (ets.ETS_PLAN_TREE, {"cascade_min_leaves": 0}),
+    "tree_valu_only": (ets.ETS_PLAN_TREE, {"mfma": 0}),
     "flat": (ets.ETS_PLAN_FLAT, {}),
 }
 
@@ -40,9 +41,12 @@ def test_configs_full_parity(name, variant):
     cfg = CONFIGS[name]
     _, st = _run_full(cfg, make_tree(cfg), variant, name)
     if variant == "tree" and cfg.dtype == "bf16":
-        assert st.n_cascade_items > 0 and st.cascade_tokens > 0     # the MFMA path ran
-    if variant != "tree":
+        assert st.n_cascade_items > 0 and st.cascade_tokens > 0     # shared nodes on the MFMA path
+        assert st.n_stream_items == 0
+    if variant == "tree_valu_only" or cfg.dtype == "f32":
         assert st.n_cascade_items == 0
+    if variant in ("flat", "tree_no_sharing"):
+        assert st.cascade_tokens == 0
 
 
 @pytest.mark.parametrize("variant", ["tree", "flat"])
@@ -90,7 +94,8 @@ def test_fuzz_irregular_forests(seed):
     hkv, hq, d, dt = SHAPES[seed % len(SHAPES)]
     cfg = TreeConfig("fuzz", hkv, hq, d, dt, 0, 0, 0, 0, 0, None, seed=900 + seed)
     tree = random_tree(seed, n_nodes=50, n_leaves=21, max_tokens=90)
-    options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3]}
+    options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3],
+               "cascade_rows": [128, 32, 64][(seed // 2) % 3]}
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):

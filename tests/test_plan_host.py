@@ -78,9 +78,12 @@ def test_plan_indexing_matches_oracle_on_configs(name, mode):
         leaves = None if t.n_leaves <= 64 else list(range(0, t.n_leaves, t.n_leaves // 32))
         st = _check_plan_against_oracle(ctx, t, mode, leaves)
         if mode == ets.ETS_PLAN_FLAT:
-            assert st.n_cascade_items == 0
+            assert st.cascade_tokens == 0           # nothing is shared in the flat baseline
+            assert st.stream_tokens == st.flat_tokens
         elif cfg.dtype == "bf16":
-            assert st.n_cascade_items > 0
+            assert st.cascade_tokens > 0
+        else:
+            assert st.n_cascade_items == 0          # fp32 pools take the streaming kernel
 
 
 def test_c1_closed_form_counts():
@@ -101,6 +104,7 @@ def test_plan_fuzz_irregular_forests(seed):
         ctx.set_option("cascade_min_leaves", 2)
         ctx.set_option("stream_chunk", [0, 32, 64][seed % 3])
         ctx.set_option("cascade_chunk", [0, 32, 96][(seed // 3) % 3])
+        ctx.set_option("mfma", 0 if seed % 4 == 3 else 1)
         for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
             _check_plan_against_oracle(ctx, t, mode)
 
@@ -176,5 +180,6 @@ def test_sharing_reduces_partials_and_flat_is_per_leaf():
         tree = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, ets.ETS_PLAN_TREE).as_dict()
         flat = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, ets.ETS_PLAN_FLAT).as_dict()
     assert tree["unique_tokens"] == flat["unique_tokens"]
-    assert flat["n_cascade_items"] == 0 and flat["n_stream_items"] >= t.n_leaves
-    assert tree["n_cascade_items"] > 0
+    assert flat["cascade_tokens"] == 0
+    assert flat["n_cascade_items"] + flat["n_stream_items"] >= t.n_leaves
+    assert tree["cascade_tokens"] > 0 and tree["n_partials"] > flat["n_partials"]
