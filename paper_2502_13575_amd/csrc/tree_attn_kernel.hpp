@@ -63,10 +63,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void t
     __shared__ u32x4_t smem[KS_UNITS + VS_UNITS];
     __shared__ float sm_m[4][NB][16];
     __shared__ float sm_l[4][NB][16];
+    __shared__ int sm_n[4];  // tokens in each of the staged tile's four steps (0 = none)
     u32x4_t* ks = smem;
     u32x4_t* vs = smem + KS_UNITS;
 
-    const int w = threadIdx.x >> 6;
+    // wave index, made known-uniform so that per-wave descriptors come through scalar loads
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int a = lane & 15;  // 16-byte piece of a row when loading; MFMA row/column index
     const int b = lane >> 4;  // token sub-index when loading; MFMA contraction group kg
@@ -108,12 +110,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void t
         for (int x = 0; x < 8; ++x) oacc[blk][x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    // wave w fetches step 4 tile + w of every tile
+    // wave w fetches step 4 tile + w of every tile; the step descriptor is read one
+    // tile ahead of the loads that use it
     u32x4_t kraw[8], vraw[8];
-    auto issue_loads = [&](int tile) {
+    auto read_desc = [&](int tile) {
         const int sidx = 4 * tile + w;
-        if (sidx < n_steps) {
-            const Run sd = my_steps[sidx];
+        return sidx < n_steps ? my_steps[sidx] : Run{0, 0, 0};
+    };
+    auto issue_loads = [&](const Run& sd) {
+        if (sd.n > 0) {
             const int last = sd.n - 1;
             const int64_t base = (sd.tok * n_kv_heads + h) * (int64_t)D + a * 8;
             const bf16_t* kb = k_pool + base;
@@ -127,8 +132,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void t
             }
         }
     };
-    auto stage = [&](int tile) {
-        if (4 * tile + w < n_steps) {
+    auto stage = [&](const Run& sd) {
+        if (lane == 0) sm_n[w] = sd.n;
+        if (sd.n > 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) ks[(32 * w + 4 * i + b) * KROW + a] = kraw[i];
 #pragma unroll
@@ -143,20 +149,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void t
         }
     };
 
-    issue_loads(0);
-    stage(0);
+    Run sd_loaded = read_desc(0);  // descriptor of the loads in flight
+    issue_loads(sd_loaded);
+    Run sd_next = read_desc(1);
+    stage(sd_loaded);
+    // Everything issued so far (Q rows, first tile) has to have landed on every path
+    // before the loop: a load still counted as outstanding here would make each
+    // iteration wait for the next tile's loads as well.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
     for (int tile = 0; tile < n_tiles; ++tile) {
-        if (tile + 1 < n_tiles) issue_loads(tile + 1);
+        sd_loaded = sd_next;         // tile + 1 (a descriptor past the end has n = 0)
+        issue_loads(sd_loaded);
+        sd_next = read_desc(tile + 2);
 
         const int st_lo = rowpar ? 0 : w;
         const int st_hi = rowpar ? 4 : w + 1;
 #pragma unroll 1
         for (int st = st_lo; st < st_hi; ++st) {
-            const int sidx = 4 * tile + st;
-            if (sidx >= n_steps || nbv == 0) break;
-            const int n_valid = my_steps[sidx].n;
+            const int n_valid = __builtin_amdgcn_readfirstlane(sm_n[st]);
+            if (n_valid == 0 || nbv == 0) break;
 
             // scores S^T = K Q^T of every row block; K fragments come from the LDS
             // tile one at a time and serve all blocks
@@ -255,7 +268,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void t
         }
 
         __syncthreads();  // every wave is done reading the staged tile
-        if (tile + 1 < n_tiles) stage(tile + 1);
+        stage(sd_loaded);
         __syncthreads();
     }
 
