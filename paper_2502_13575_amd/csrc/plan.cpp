@@ -31,6 +31,8 @@ struct Chunk {
     int32_t run_begin, run_end, tokens;
 };
 
+constexpr int64_t kMaxPiecesPerChunk = 512;  // step list the matrix-core kernel keeps in LDS
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
 
@@ -65,14 +67,17 @@ void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
     int64_t left = tokens;
     while (left > 0) {
         int64_t want = std::min(per, left);
-        Chunk c{(int32_t)p.runs.size(), 0, (int32_t)want};
-        while (want > 0) {
+        Chunk c{(int32_t)p.runs.size(), 0, 0};
+        int64_t pieces = 0;
+        while (want > 0 && (piece <= 0 || pieces < kMaxPiecesPerChunk)) {
             const int64_t avail = src[ri].n - used;
             int64_t take = std::min(avail, want);
             if (piece > 0) take = std::min(take, piece);
             p.runs.push_back(Run{src[ri].tok + used, (int32_t)take, 0});
             used += take;
             want -= take;
+            c.tokens += (int32_t)take;
+            ++pieces;
             if (used == src[ri].n) {
                 ++ri;
                 used = 0;
@@ -205,10 +210,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // cost model in nanoseconds per tile of 128 tokens: a workgroup that is
     // waiting on memory needs about t_mem per tile; one that computes needs
     // t_blk per 32-token step and 16-row block of its busiest wave
-    const int64_t t_mem = 1200, t_blk = 220;
+    const int64_t t_mem = 2200, t_blk = 700;
     auto tile_cost = [&](int64_t rows) {
         if (rows <= 32) return t_mem;
-        const int64_t blocks_per_wave = std::min<int64_t>(2, ceil_div(ceil_div(rows, 16), 4));
+        const int64_t blocks_per_wave = ceil_div(ceil_div(rows, 16), 4);
         return std::max(t_mem, 4 * blocks_per_wave * t_blk);
     };
     int64_t own_total = 0, work_ns = 0;
@@ -228,10 +233,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         }
     }
     // time the whole call is expected to take: the larger of the HBM time of the
-    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 256 compute
-    // units; no single item should take more than a third of it
+    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 512 resident
+    // workgroups; no single item should take more than a third of it
     const int64_t hbm_ns = st.unique_kv_bytes / 5500;
-    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 256) / 3, 4 * t_mem);
+    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 512) / 3, 4 * t_mem);
 
     int64_t scap = opt.stream_chunk;
     if (scap <= 0) {

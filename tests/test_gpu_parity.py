@@ -163,3 +163,21 @@ def test_device_error_paths():
             ctx.decode(k.data_ptr() + 4, v, 256, q, out, lse, ws, st.workspace_bytes)
         assert e.value.status == 1                      # misaligned pool
         assert torch.all(out == 0) and torch.all(lse == 0)   # outputs untouched on error
+
+
+def test_long_chain_of_one_token_nodes():
+    n = 1500
+    parent = np.arange(-1, n - 1, dtype=np.int32)
+    n_tok = np.ones(n, np.int32)
+    off = (np.arange(n, dtype=np.int64) * 7919) % n
+    leaf = np.array([n - 1, n - 1, 700], np.int32)
+    from workload import Tree
+    tree = Tree(parent, off, n_tok, leaf, n)
+    cfg = TreeConfig("chain", 2, 8, 128, "bf16", 0, 0, 0, 0, 0, None, seed=31)
+    k, v, q = make_values_host(cfg, tree)
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    print("case one-token chain", flush=True)
+    with make_ctx(cfg) as ctx:
+        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q))
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "chain")

@@ -183,3 +183,20 @@ def test_sharing_reduces_partials_and_flat_is_per_leaf():
     assert flat["cascade_tokens"] == 0
     assert flat["n_cascade_items"] + flat["n_stream_items"] >= t.n_leaves
     assert tree["cascade_tokens"] > 0 and tree["n_partials"] > flat["n_partials"]
+
+
+def test_long_chain_of_one_token_nodes_is_cut_into_bounded_step_lists():
+    # 1500 single-token nodes scattered in the pool: every node is its own step,
+    # more than one work item can list
+    n = 1500
+    parent = np.arange(-1, n - 1, dtype=np.int32)
+    n_tok = np.ones(n, np.int32)
+    off = (np.arange(n, dtype=np.int64) * 7919) % n            # a permutation of the rows
+    leaf = np.array([n - 1, n - 1, 700], np.int32)
+    with _ctx((2, 8, 128, ets.ETS_BF16)) as ctx:
+        st = ctx.plan(parent, off, n_tok, leaf)
+        assert st.n_partials >= 3 + 2                          # the chain had to be chunked
+        for l in range(3):
+            rows, _ = ctx.leaf_cover(l)
+            want = off[:leaf[l] + 1]
+            assert np.array_equal(np.sort(rows), np.sort(want))
