@@ -20,6 +20,25 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary, or None when the kernel or planner changed since it was taken."""
+    import hashlib
+    import os
+    root = os.path.dirname(os.path.abspath(__file__))
+    path = os.path.join(root, "profiles", "traffic_tree_attn_%s.json" % workload)
+    try:
+        rec = json.load(open(path))
+        h = hashlib.sha256()
+        for f in ("tree_attn_kernel.hpp", "plan.cpp"):
+            h.update(open(os.path.join(root, "paper_2502_13575_amd", "csrc", f), "rb").read())
+        if h.hexdigest()[:16] != rec["source_sha256_16"]:
+            return None
+        return int(rec["hbm_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -34,6 +53,9 @@ def main():
                     help="CPU time budget of the oracle baseline sample (0 = skip)")
     ap.add_argument("--flat-steps", type=int, default=2, help="timed steps of the flat baseline (0 = skip)")
     ap.add_argument("--option", action="append", default=[], help="planner knob key=value")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size reference for "
+                         "scaling hardware byte counters when profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -102,6 +124,15 @@ def main():
         ctx.set_option("profile", 0)
         return el, prof
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.zero_()
+        torch.cuda.synchronize()
+        dst.copy_(src)              # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     elapsed, prof = timed(args.warmup, args.steps, st)
     ms_per_step = elapsed / args.steps * 1e3
     calls = args.steps * cfg.layers
@@ -109,20 +140,24 @@ def main():
     tok_bytes = 2 * cfg.n_kv_heads * cfg.head_dim * cfg.elem_bytes
     unique_gbps = st.unique_kv_bytes * calls / elapsed / 1e9
 
-    # roofline of the dominant kernel: its own algorithmic KV bytes per launch
+    # roofline of the dominant kernel: the algorithmic KV bytes of the items it reads
+    # (unique tokens x 2 x Hkv x D x element size, each read once per launch)
+    mfma_path = st.n_cascade_items > 0
     kern = {
-        "cascade": (prof.cascade_ms, st.cascade_tokens * tok_bytes),
-        "stream": (prof.stream_ms, (st.unique_tokens - st.cascade_tokens) * tok_bytes),
+        "cascade": (prof.cascade_ms, st.unique_tokens * tok_bytes if mfma_path else 0),
+        "stream": (prof.stream_ms, 0 if mfma_path else st.unique_tokens * tok_bytes),
     }
     dom = max(kern, key=lambda k: kern[k][0])
     dom_ms = kern[dom][0] / max(prof.calls, 1)
     achieved = kern[dom][1] / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
+    kernel_name = {"cascade": "tree_attn_kernel", "stream": "stream_attn_kernel"}
+    roofline = {"bound": "hbm", "kernel": kernel_name[dom], "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": None, "avg_launch_us": round(dom_ms * 1e3, 2),
+                "traffic": measured_traffic(cfg.name) if dom == "cascade" else None,
+                "avg_launch_us": round(dom_ms * 1e3, 2),
                 "algorithmic_bytes_per_launch": int(kern[dom][1])}
-    kernel_us = {"stream": round(prof.stream_ms / max(prof.calls, 1) * 1e3, 2),
-                 "cascade": round(prof.cascade_ms / max(prof.calls, 1) * 1e3, 2),
+    kernel_us = {"stream_attn": round(prof.stream_ms / max(prof.calls, 1) * 1e3, 2),
+                 "tree_attn": round(prof.cascade_ms / max(prof.calls, 1) * 1e3, 2),
                  "merge": round(prof.merge_ms / max(prof.calls, 1) * 1e3, 2)}
     log("tree: %.3f ms/step, %.0f leaf-queries/s, unique-KV %.0f GB/s (%.1f%% of peak); "
         "kernels per layer (us): %s" % (ms_per_step, leaf_q_per_s, unique_gbps,
