@@ -255,7 +255,7 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
     else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
     else if (!std::strcmp(key, "cascade_min_leaves")) ctx->opt.cascade_min_leaves = value;
     else if (!std::strcmp(key, "cascade_rows")) {
-        if (value != 32 && value != 64 && value != 128) return ETS_ERR_INVALID_ARG;
+        if (value != 16 && value != 32 && value != 64) return ETS_ERR_INVALID_ARG;
         ctx->opt.cascade_rows = value;
     } else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
     else if (!std::strcmp(key, "profile")) {

@@ -31,7 +31,7 @@ struct Chunk {
     int32_t run_begin, run_end, tokens;
 };
 
-constexpr int64_t kMaxPiecesPerChunk = 512;  // step list the matrix-core kernel keeps in LDS
+constexpr int64_t kMaxPiecesPerChunk = 256;  // step list the matrix-core kernel keeps in LDS
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
@@ -207,15 +207,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     const int64_t piece = use_mfma ? 32 : 0;
     const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
     const int64_t ent_per_item = std::max<int64_t>(1, opt.cascade_rows / G);
-    // cost model in nanoseconds per tile of 128 tokens: a workgroup that is
-    // waiting on memory needs about t_mem per tile; one that computes needs
-    // t_blk per 32-token step and 16-row block of its busiest wave
-    const int64_t t_mem = 2200, t_blk = 700;
-    auto tile_cost = [&](int64_t rows) {
-        if (rows <= 32) return t_mem;
-        const int64_t blocks_per_wave = ceil_div(ceil_div(rows, 16), 4);
-        return std::max(t_mem, 4 * blocks_per_wave * t_blk);
-    };
+    // cost model in nanoseconds per tile of 64 tokens: a workgroup needs about
+    // t_tile per tile whether it waits on memory (few rows) or computes (many rows)
+    const int64_t t_tile = 1500, t_mem = t_tile, kTile = 64;
+    auto tile_cost = [&](int64_t) { return t_tile; };
     int64_t own_total = 0, work_ns = 0;
     for (Seg& sg : segs) {
         sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
@@ -224,24 +219,24 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         if (sg.cascade) {
             st.cascade_tokens += sg.tokens;
             for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item)
-                work_ns += ceil_div(sg.tokens, 128) *
+                work_ns += ceil_div(sg.tokens, kTile) *
                            tile_cost(std::min(ent_per_item, sg.cnt - e0) * G) * shape.n_kv_heads;
         } else {
             st.stream_tokens += sg.tokens * sg.cnt;
             own_total += sg.tokens * sg.cnt;
-            work_ns += ceil_div(sg.tokens, 128) * t_mem * sg.cnt * shape.n_kv_heads;
+            work_ns += ceil_div(sg.tokens, kTile) * t_mem * sg.cnt * shape.n_kv_heads;
         }
     }
     // time the whole call is expected to take: the larger of the HBM time of the
-    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 512 resident
+    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 1024 resident
     // workgroups; no single item should take more than a third of it
     const int64_t hbm_ns = st.unique_kv_bytes / 5500;
-    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 512) / 3, 4 * t_mem);
+    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 1024) / 3, 4 * t_mem);
 
     int64_t scap = opt.stream_chunk;
     if (scap <= 0) {
         if (use_mfma) {
-            scap = item_budget_ns / t_mem * 128;
+            scap = item_budget_ns / t_mem * kTile;
         } else {
             scap = round_up(ceil_div(own_total * shape.n_kv_heads, 2048), 32);
             scap = std::min<int64_t>(std::max<int64_t>(scap, 64), 2048);
@@ -258,7 +253,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         if (!sg.cascade) continue;
         int64_t ccap = opt.cascade_chunk;
         if (ccap <= 0)
-            ccap = item_budget_ns / tile_cost(std::min(ent_per_item, sg.cnt) * G) * 128;
+            ccap = item_budget_ns / tile_cost(std::min(ent_per_item, sg.cnt) * G) * kTile;
         tmp_runs.clear();
         collect_runs(p, sg.nodes, tmp_runs);
         cut_runs(p, tmp_runs, sg.tokens, ccap, piece, seg_chunks[s]);
@@ -295,7 +290,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 if (use_mfma) {
                     p.cascade_items.push_back(CascadeItem{c.run_begin, c.run_end, ent_pos[l], 1,
                                                           shared_slots + c_idx, c.tokens, 0, 0});
-                    cascade_cost.push_back(ceil_div(c.tokens, 128) * t_mem);
+                    cascade_cost.push_back(ceil_div(c.tokens, kTile) * t_mem);
                     p.max_cascade_ent = std::max(p.max_cascade_ent, 1);
                 } else {
                     p.stream_items.push_back(
@@ -319,7 +314,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 p.cascade_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
                                                       sg.ent_begin + (int32_t)e0, ne,
                                                       sg.prefix + c, ch.tokens, 0, 0});
-                cascade_cost.push_back(ceil_div(ch.tokens, 128) * tile_cost((int64_t)ne * G));
+                cascade_cost.push_back(ceil_div(ch.tokens, kTile) * tile_cost((int64_t)ne * G));
                 p.max_cascade_ent = std::max(p.max_cascade_ent, ne);
             }
         }

@@ -46,7 +46,7 @@ struct CascadeItem {
 struct PlanOptions {
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
-    int64_t cascade_rows = 128;      // query rows per shared work item (32, 64 or 128)
+    int64_t cascade_rows = 64;       // query rows per shared work item (16, 32 or 64)
     int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
 };

@@ -95,7 +95,7 @@ def test_fuzz_irregular_forests(seed):
     cfg = TreeConfig("fuzz", hkv, hq, d, dt, 0, 0, 0, 0, 0, None, seed=900 + seed)
     tree = random_tree(seed, n_nodes=50, n_leaves=21, max_tokens=90)
     options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3],
-               "cascade_rows": [128, 32, 64][(seed // 2) % 3]}
+               "cascade_rows": [64, 16, 32][(seed // 2) % 3]}
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
