@@ -20,31 +20,64 @@ __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ 
                                                     float* __restrict__ out,
                                                     float* __restrict__ lse) {
     constexpr int EPL = D / 64;  // floats per lane
+    struct alignas(4 * EPL) RowPiece {
+        float f[EPL];
+    };
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int64_t pair = (int64_t)blockIdx.x * 4 + wave;  // (leaf, head) index
     if (pair >= (int64_t)n_leaves * n_q_heads) return;
     const int leaf = (int)(pair / n_q_heads), j = (int)(pair % n_q_heads);
     const int p0 = part_base[leaf], p1 = part_base[leaf + 1];
 
+    // Lanes first take one partial each (its m and l), so that the maximum and the
+    // weights of up to 64 partials cost one round trip; the weighted rows are then
+    // accumulated four at a time with the weight read from the owning lane.
     float ms = -INFINITY;
-    for (int p = p0; p < p1; ++p) ms = fmaxf(ms, ws_ml[(int64_t)p * n_q_heads + j].x);
+    for (int c0 = p0; c0 < p1; c0 += 64) {
+        const int p = c0 + lane;
+        float mv = p < p1 ? ws_ml[(int64_t)p * n_q_heads + j].x : -INFINITY;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mv = fmaxf(mv, __shfl_xor(mv, off, 64));
+        ms = fmaxf(ms, mv);
+    }
 
     float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
     float ls = 0.f;
-    for (int p = p0; p < p1; ++p) {
-        const int64_t row = (int64_t)p * n_q_heads + j;
-        const float2 ml = ws_ml[row];
-        const float w = fast_exp2(ml.x - ms);
-        ls = fmaf(ml.y, w, ls);
-        const float* src = ws_o + row * D + lane * EPL;
-        if constexpr (EPL == 2) {
-            const float2 v = *reinterpret_cast<const float2*>(src);
-            acc[0] = fmaf(v.x, w, acc[0]);
-            acc[1] = fmaf(v.y, w, acc[1]);
-        } else {
-            acc[0] = fmaf(src[0], w, acc[0]);
+    for (int c0 = p0; c0 < p1; c0 += 64) {
+        const int p = c0 + lane;
+        float wv = 0.f, lw = 0.f;
+        if (p < p1) {
+            const float2 ml = ws_ml[(int64_t)p * n_q_heads + j];
+            wv = fast_exp2(ml.x - ms);
+            lw = ml.y * wv;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) lw += __shfl_xor(lw, off, 64);
+        ls += lw;
+        const int cn = min(64, p1 - c0);
+        const float* base = ws_o + ((int64_t)c0 * n_q_heads + j) * D + lane * EPL;
+        const int64_t stride = (int64_t)n_q_heads * D;
+        int k = 0;
+        for (; k + 4 <= cn; k += 4) {
+            RowPiece v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = *reinterpret_cast<const RowPiece*>(base + (k + u) * stride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float w = __builtin_bit_cast(
+                    float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), k + u));
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[i] = fmaf(v[u].f[i], w, acc[i]);
+            }
+        }
+        for (; k < cn; ++k) {
+            const float w =
+                __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), k));
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(base[k * stride + i], w, acc[i]);
         }
     }
     const bool empty = p1 == p0;
