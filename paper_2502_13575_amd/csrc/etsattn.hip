@@ -1,6 +1,7 @@
 // C ABI of libetsattn (see include/etsattn.h) and the kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -154,12 +155,15 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     if (n_items <= 0) return;
     const int g = c->shape.n_q_heads / c->shape.n_kv_heads;
     const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
-    const unsigned grid = (unsigned)(n_items * c->shape.n_kv_heads);
-    hipLaunchKernelGGL(tree_attn_kernel, dim3(grid), dim3(256), 0, a.stream,
-                       static_cast<const bf16_t*>(a.k), static_cast<const bf16_t*>(a.v),
-                       static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_ent_order,
-                       c->d_part_base, c->shape.n_kv_heads, g_shift,
-                       c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+    // grid: x = kv head, y = work item (at most 65535 per launch)
+    for (int64_t i0 = 0; i0 < n_items; i0 += 65535) {
+        const unsigned ny = (unsigned)std::min<int64_t>(65535, n_items - i0);
+        hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0,
+                           a.stream, static_cast<const bf16_t*>(a.k),
+                           static_cast<const bf16_t*>(a.v), static_cast<const bf16_t*>(a.q),
+                           c->d_runs, c->d_cascade + i0, c->d_ent_order, c->d_part_base, g_shift,
+                           c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+    }
 }
 
 constexpr size_t kMaxProfiledCalls = 8192;

@@ -139,20 +139,71 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
     lsum += psum;
 }
 
+// Token-parallel unit: the 16 tokens one wave fetched itself, against the single
+// block of query rows.  K rows and transposed V pieces sit in the wave's own LDS
+// region.  The weight enters the P V product as a bf16 head in contraction slots
+// 0..3 and its bf16 remainder in slots 4..7, against the same four V rows in both
+// slot halves, so one MFMA per fragment applies both.
+__device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_lane,
+                                               const u32x2_t* __restrict__ vs_lane, int b,
+                                               int n_valid, const bf16x8_t (&qf)[4],
+                                               f32x4_t (&oacc)[8], float& m, float& lsum,
+                                               float scale_log2e, float raise_margin) {
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[4 * kk]), qf[kk], s, 0, 0, 0);
+    // lane holds row a, tokens 4 b + i; masking is unconditional so that the scores are
+    // consumed in straight-line code after the matrix instructions
+    const int rem = n_valid - 4 * b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[i] = i < rem ? s[i] : -INFINITY;
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    if (__any(mx > m + raise_margin)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2((m - m_new) * scale_log2e);
+        lsum *= alpha;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) oacc[x] *= alpha;
+        m = m_new;
+    }
+    const float mc = m * scale_log2e;
+    float psum = 0.f;
+    bf16x8_t pf;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float p = fast_exp2(fmaf(s[i], scale_log2e, -mc));
+        psum += p;
+        const __bf16 hi = (__bf16)p;
+        pf[i] = hi;
+        pf[4 + i] = (__bf16)(p - (float)hi);
+    }
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const u32x2_t t = vs_lane[x * 64];
+        const u32x4_t vf = {t[0], t[1], t[0], t[1]};
+        oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf), pf, oacc[x], 0, 0, 0);
+    }
+    lsum += psum;
+}
+
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
     const CascadeItem* __restrict__ items, const int32_t* __restrict__ ent_order,
-    const int32_t* __restrict__ part_base, int n_kv_heads, int g_shift, float scale_log2e,
+    const int32_t* __restrict__ part_base, int g_shift, float scale_log2e,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
     constexpr int D = 128;
+    const int n_kv_heads = (int)gridDim.x;
     constexpr int KROW = kTreeAttnKRow;
     constexpr int KS_UNITS = 64 * KROW;    // K tile: 64 padded rows
     constexpr int VS_UNITS = 2 * 8 * 64;   // V^T fragments: [step][x][lane]
     // K tile, then V^T fragments; the K part is reused for the token-parallel fold
     __shared__ u32x4_t smem[KS_UNITS + VS_UNITS];
-    __shared__ float sm_m[2][16];
-    __shared__ float sm_l[2][16];
+    __shared__ float sm_m[4][16];
+    __shared__ float sm_l[4][16];
     __shared__ u32x4_t sm_desc[kTreeAttnMaxSteps];  // the item's step list
     u32x4_t* ks = smem;
     u32x4_t* vs = smem + KS_UNITS;
@@ -164,8 +215,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int lane = threadIdx.x & 63;
     const int a = lane & 15;  // 16-byte piece of a row when loading; MFMA row/column index
     const int b = lane >> 4;  // token sub-index when loading; MFMA contraction group kg
-    const int h = blockIdx.x % n_kv_heads;
-    const CascadeItem it = items[blockIdx.x / n_kv_heads];
+    const int h = blockIdx.x;  // kv head; consecutive workgroups share an item
+    const CascadeItem it = items[blockIdx.y];
     const int G = 1 << g_shift;
     const int n_q_heads = n_kv_heads << g_shift;
     const int R = it.n_ent << g_shift;
@@ -173,7 +224,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int n_blocks = (R + 15) >> 4;
     // the row block this wave computes: block w when row parallel, block 0 otherwise
     const int blk = rowpar ? w : 0;
-    const bool computes = rowpar ? (w < n_blocks) : (hw == 0);
+    const bool computes = w < n_blocks;  // row parallel only; token parallel: every wave
+    // a token-parallel wave needs its half of a step only if the step reaches it
+    const int load_min = rowpar ? 0 : 16 * hw;
     const int n_steps = it.run_end - it.run_begin;
     const int n_tiles = (n_steps + 1) >> 1;
     const Run* my_steps = steps + it.run_begin;
@@ -185,56 +238,70 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // K: token 16 hw + 4 i + b;  V: contraction slot 4 hw + j of group b = token 16 hw + 4 b + j
     const uint32_t k_lane_off = (uint32_t)(16 * hw + b) * stride_b + a * 16;
     const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + a * 16;
+    // Buffer loads: a step's rows are addressed through a descriptor that covers exactly
+    // the step (base = its first row at this kv head, size = n rows), so a load is a
+    // scalar descriptor plus a 32-bit lane offset, and rows past the end of a ragged step
+    // read as zero instead of needing clamped addresses (they are masked later).
     auto issue_loads = [&](const Run& sd) {
-        if (sd.n > 0) {
+        if (sd.n > load_min) {
             const int64_t base = (sd.tok * n_kv_heads + h) * (int64_t)D * 2;
-            const char* kb = reinterpret_cast<const char*>(k_pool) + base;  // uniform
-            const char* vb = reinterpret_cast<const char*>(v_pool) + base;
+            char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;  // uniform
+            char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
+            const int bytes = sd.n * (int)stride_b;
+            const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(kb, 0, bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(vb, 0, bytes, 0x00020000);
             if (sd.n == 32) {
-                // full step: uniform base + per-lane offset that never changes
+                // full step: every row is in range; the row stepping rides in the scalar offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = load16(kb + (uint32_t)(4 * i) * stride_b + k_lane_off);
-                    vraw[i] = load16(vb + (uint32_t)i * stride_b + v_lane_off);
+                    kraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                              kr, k_lane_off, 4 * i * (int)stride_b, 0));
+                    vraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                              vr, v_lane_off, i * (int)stride_b, 0));
                 }
             } else {
-                // ragged tail of a run: rows past the end re-read the last row (masked later)
-                const int last = sd.n - 1;
+                // ragged step: the whole offset is in the range-checked lane offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const uint32_t tk = (uint32_t)min(16 * hw + 4 * i + b, last);
-                    const uint32_t tv = (uint32_t)min(16 * hw + 4 * b + i, last);
-                    kraw[i] = load16(kb + tk * stride_b + a * 16);
-                    vraw[i] = load16(vb + tv * stride_b + a * 16);
+                    kraw[i] = __builtin_bit_cast(
+                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                     kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0, 0));
+                    vraw[i] = __builtin_bit_cast(
+                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                     vr, v_lane_off + (uint32_t)i * stride_b, 0, 0));
                 }
             }
         }
     };
 
-    // The first tile's loads start as soon as this wave's first step is known (read
-    // straight from the step list); everything else the prologue needs overlaps them.
+    // Prologue loads, in the order their results are needed (vector loads return in
+    // order): the lane's query index, the first tile, the step list, then the query
+    // row, which depends on the first.
+    const int r_lane = 16 * blk + a;
+    const int rr = r_lane < R ? r_lane : 0;  // padding rows read a valid row; never written
+    const int ent = ent_order[it.ent_begin + (rr >> g_shift)];
+
     Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
     issue_loads(sd_loaded);
 
     // the item's step descriptors go to LDS once; nothing but K, V is fetched afterwards
+    u32x4_t desc_raw = {0u, 0u, 0u, 0u};
     if ((int)threadIdx.x < n_steps)
-        sm_desc[threadIdx.x] = load16(reinterpret_cast<const char*>(my_steps + threadIdx.x));
+        desc_raw = load16(reinterpret_cast<const char*>(my_steps + threadIdx.x));
 
     // Q rows as B operands: lane (column a = query row, group b) holds
     // q[row][32 kk + 8 b .. + 8) for kk = 0..3.  The workspace row of the lane's
     // partial result is looked up here as well, off the critical path.
     bf16x8_t qf[4];
     int32_t out_row;
-    const int r_lane = 16 * blk + a;
     {
-        const int rr = r_lane < R ? r_lane : 0;  // padding rows read a valid row; never written
-        const int ent = ent_order[it.ent_begin + (rr >> g_shift)];
         const int head = h * G + (rr & (G - 1));
         const bf16_t* qp = q + ((int64_t)ent * n_q_heads + head) * D;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
         out_row = (part_base[ent] + it.slot_off) * n_q_heads + head;
     }
+    if ((int)threadIdx.x < n_steps) sm_desc[threadIdx.x] = desc_raw;
 
     f32x4_t oacc[8];
     float m = -INFINITY, lsum = 0.f;
@@ -256,88 +323,123 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         if (sd.n > 0) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = kraw[i];
-            // this half's four contraction slots of every V^T fragment: 8 of its 16 bytes
+            // This half's four contraction slots of every V^T fragment (8 of its 16
+            // bytes), converted to fp16 for the P V product once for all row blocks:
+            // element x of the lane's 16-byte piece, tokens 4 b .. 4 b + 3.
             u32x2_t* vs2 = reinterpret_cast<u32x2_t*>(vs);
 #pragma unroll
-            for (int x = 0; x < 8; ++x) {
-                const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-                u32x2_t t;
-                t[0] = __builtin_amdgcn_perm(vraw[1][x >> 1], vraw[0][x >> 1], sel);
-                t[1] = __builtin_amdgcn_perm(vraw[3][x >> 1], vraw[2][x >> 1], sel);
-                if (rowpar) {
-                    // shared by several row blocks: convert once to fp16 for the P V product
-                    t[0] = bf16x2_to_f16x2(t[0]);
-                    t[1] = bf16x2_to_f16x2(t[1]);
-                }
-                vs2[((sw * 8 + x) * 64 + lane) * 2 + hw] = t;
+            for (int j = 0; j < 4; ++j) {
+                u32x2_t te, to;
+                te[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
+                                                         bf16_lo(vraw[0][j]), bf16_lo(vraw[1][j])));
+                te[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
+                                                         bf16_lo(vraw[2][j]), bf16_lo(vraw[3][j])));
+                to[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
+                                                         bf16_hi(vraw[0][j]), bf16_hi(vraw[1][j])));
+                to[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
+                                                         bf16_hi(vraw[2][j]), bf16_hi(vraw[3][j])));
+                vs2[((sw * 8 + 2 * j) * 64 + lane) * 2 + hw] = te;
+                vs2[((sw * 8 + 2 * j + 1) * 64 + lane) * 2 + hw] = to;
             }
         }
     };
 
-    stage(sd_loaded);
-    // Everything issued so far (Q rows, first tile) has to have landed on every path
-    // before the loop: a load still counted as outstanding here would make each
-    // iteration wait for the next tile's loads as well.
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();  // step list and first tile are in LDS
-
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        sd_loaded = read_desc(2 * (tile + 1) + sw);  // a step past the end has n = 0
-        issue_loads(sd_loaded);
-
-        if (computes) {
-            const int st_lo = rowpar ? 0 : sw;
-            const int st_hi = rowpar ? 2 : sw + 1;
-#pragma unroll 1
-            for (int st = st_lo; st < st_hi; ++st) {
-                const int sidx = 2 * tile + st;
-                if (sidx >= n_steps) break;
-                const int n_valid = __builtin_amdgcn_readfirstlane(sm_desc[sidx][2]);
-                const u32x4_t* ks_lane = ks + (32 * st + a) * KROW + b;
-                const u32x4_t* vs_lane = vs + st * 8 * 64 + lane;
-                if (rowpar)
-                    attn_step<true>(ks_lane, vs_lane, b, n_valid, qf, oacc, m, lsum, scale_log2e,
-                                    raise_margin);
-                else
-                    attn_step<false>(ks_lane, vs_lane, b, n_valid, qf, oacc, m, lsum, scale_log2e,
-                                     raise_margin);
-            }
-        }
-
-        __syncthreads();  // the staged tile has been read by everyone who shares it
+    if (rowpar) {
         stage(sd_loaded);
-        __syncthreads();
+        // Everything issued so far (Q rows, first tile) has to have landed on every path
+        // before the loop: a load still counted as outstanding here would make each
+        // iteration wait for the next tile's loads as well.
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();  // step list and first tile are in LDS
+
+        for (int tile = 0; tile < n_tiles; ++tile) {
+            sd_loaded = read_desc(2 * (tile + 1) + sw);  // a step past the end has n = 0
+            issue_loads(sd_loaded);
+
+            if (computes) {
+#pragma unroll 1
+                for (int st = 0; st < 2; ++st) {
+                    const int sidx = 2 * tile + st;
+                    if (sidx >= n_steps) break;
+                    const int n_valid = __builtin_amdgcn_readfirstlane(sm_desc[sidx][2]);
+                    attn_step<true>(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
+                                    n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
+                }
+            }
+
+            __syncthreads();  // the staged tile has been read by everyone who shares it
+            stage(sd_loaded);
+            __syncthreads();
+        }
+        if (!computes) return;
+    } else {
+        // Token parallel: every wave walks its own 16-token units (half hw of step
+        // 2 tile + sw) through a private LDS region; no workgroup barrier in the loop.
+        u32x4_t* ksw = ks + 16 * w * KROW;
+        u32x2_t* vsw = reinterpret_cast<u32x2_t*>(vs) + w * (8 * 64);
+        auto stage_unit = [&](const Run& sd) {
+            if (sd.n > 16 * hw) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = kraw[i];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+                    u32x2_t t;
+                    t[0] = __builtin_amdgcn_perm(vraw[1][x >> 1], vraw[0][x >> 1], sel);
+                    t[1] = __builtin_amdgcn_perm(vraw[3][x >> 1], vraw[2][x >> 1], sel);
+                    vsw[x * 64 + lane] = t;
+                }
+            }
+        };
+        stage_unit(sd_loaded);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();  // step list is in LDS
+
+        for (int tile = 0; tile < n_tiles; ++tile) {
+            const int n_cur = sd_loaded.n - 16 * hw;  // tokens of the staged unit
+            sd_loaded = read_desc(2 * (tile + 1) + sw);
+            issue_loads(sd_loaded);
+            if (n_cur > 0)
+                attn_half_step(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
+                               scale_log2e, raise_margin);
+            // the wave's LDS accesses complete in order; keep the compiler from moving them
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            stage_unit(sd_loaded);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 
     float l = lsum;
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    float scale_o = 1.f;
     if (!rowpar) {
-        // token parallel: waves 0 and 2 hold the same rows over disjoint tokens; wave 2
-        // hands its result to wave 0 through LDS (the tile buffer is free now)
-        if (hw == 0 && b == 0) {
-            sm_m[sw][a] = m;
-            sm_l[sw][a] = l;
+        // The four waves hold the same rows over disjoint tokens (a wave that saw no
+        // token has m = -inf, l = 0); waves 1..3 hand their results to wave 0 through
+        // LDS, so the item still yields one partial per query row.
+        if (b == 0) {
+            sm_m[w][a] = m;
+            sm_l[w][a] = l;
         }
-        __syncthreads();
-        const float ms = fmaxf(sm_m[0][a], sm_m[1][a]);
-        const float f0 = fast_exp2((sm_m[0][a] - ms) * scale_log2e);
-        const float f1 = fast_exp2((sm_m[1][a] - ms) * scale_log2e);
+        __syncthreads();  // also: every wave is done with its tile region
+        const float ms = fmaxf(fmaxf(sm_m[0][a], sm_m[1][a]), fmaxf(sm_m[2][a], sm_m[3][a]));
+        const float f_own = fast_exp2((m - ms) * scale_log2e);
         f32x4_t* fold = reinterpret_cast<f32x4_t*>(smem) + lane;
-        if (w == 2) {
+        if (w != 0) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) fold[x * 64] = oacc[x] * f1;
+            for (int x = 0; x < 8; ++x) fold[((w - 1) * 8 + x) * 64] = oacc[x] * f_own;
         }
         __syncthreads();
         if (w != 0) return;
-        l = sm_l[0][a] * f0 + sm_l[1][a] * f1;
-        m = ms;
-        scale_o = f0;
+        l *= f_own;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) oacc[x] = oacc[x] * f0 + fold[x * 64];
-    } else if (!computes) {
-        return;
+        for (int k = 1; k < 4; ++k)
+            l += sm_l[k][a] * fast_exp2((sm_m[k][a] - ms) * scale_log2e);
+        m = ms;
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+            oacc[x] = oacc[x] * f_own + fold[x * 64] + fold[(8 + x) * 64] + fold[(16 + x) * 64];
     }
 
     // partial result of row a of the wave's block: lane group b holds d = 32 b + 8 i + x
@@ -352,7 +454,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         }
         if (b == 0) ws_ml[out_row] = make_float2(m * scale_log2e, l);
     }
-    (void)scale_o;
 }
 
 }  // namespace ets
