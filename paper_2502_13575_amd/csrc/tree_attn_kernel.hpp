@@ -44,6 +44,8 @@
 // units, merged later along each leaf's chain.
 #pragma once
 
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "plan.h"
 
@@ -242,7 +244,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // the step (base = its first row at this kv head, size = n rows), so a load is a
     // scalar descriptor plus a 32-bit lane offset, and rows past the end of a ragged step
     // read as zero instead of needing clamped addresses (they are masked later).
-    auto issue_loads = [&](const Run& sd) {
+    auto issue_loads = [&](const Run& sd, auto aux_tag) {
+        // cache policy of the loads: 2 = non-temporal, for rows that no other item reads
+        constexpr int kAux = decltype(aux_tag)::value;
         if (sd.n > load_min) {
             const int64_t base = (sd.tok * n_kv_heads + h) * (int64_t)D * 2;
             char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;  // uniform
@@ -255,9 +259,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     kraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                              kr, k_lane_off, 4 * i * (int)stride_b, 0));
+                                                              kr, k_lane_off, 4 * i * (int)stride_b, kAux));
                     vraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                              vr, v_lane_off, i * (int)stride_b, 0));
+                                                              vr, v_lane_off, i * (int)stride_b, kAux));
                 }
             } else {
                 // ragged step: the whole offset is in the range-checked lane offset
@@ -265,10 +269,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                 for (int i = 0; i < 4; ++i) {
                     kraw[i] = __builtin_bit_cast(
                         u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0, 0));
+                                     kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0, kAux));
                     vraw[i] = __builtin_bit_cast(
                         u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     vr, v_lane_off + (uint32_t)i * stride_b, 0, 0));
+                                     vr, v_lane_off + (uint32_t)i * stride_b, 0, kAux));
                 }
             }
         }
@@ -282,7 +286,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int ent = ent_order[it.ent_begin + (rr >> g_shift)];
 
     Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
-    issue_loads(sd_loaded);
+    if (rowpar)
+        issue_loads(sd_loaded, std::integral_constant<int, 0>{});
+    else
+        issue_loads(sd_loaded, std::integral_constant<int, 2>{});
 
     // the item's step descriptors go to LDS once; nothing but K, V is fetched afterwards
     u32x4_t desc_raw = {0u, 0u, 0u, 0u};
@@ -354,10 +361,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
 
         for (int tile = 0; tile < n_tiles; ++tile) {
             sd_loaded = read_desc(2 * (tile + 1) + sw);  // a step past the end has n = 0
-            issue_loads(sd_loaded);
+            issue_loads(sd_loaded, std::integral_constant<int, 0>{});
 
             if (computes) {
-#pragma unroll 1
+#pragma unroll
                 for (int st = 0; st < 2; ++st) {
                     const int sidx = 2 * tile + st;
                     if (sidx >= n_steps) break;
@@ -398,7 +405,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         for (int tile = 0; tile < n_tiles; ++tile) {
             const int n_cur = sd_loaded.n - 16 * hw;  // tokens of the staged unit
             sd_loaded = read_desc(2 * (tile + 1) + sw);
-            issue_loads(sd_loaded);
+            issue_loads(sd_loaded, std::integral_constant<int, 2>{});
             if (n_cur > 0)
                 attn_half_step(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
                                scale_log2e, raise_margin);
