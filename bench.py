@@ -39,6 +39,27 @@ def measured_traffic(workload):
         return None
 
 
+def record_traffic(workload, fetch_kib, write_kib, fetch_scale, write_scale):
+    """Writes profiles/traffic_tree_attn_<workload>.json from `rocprofv3 --pmc FETCH_SIZE`
+    and `--pmc WRITE_SIZE` readings (KiB per launch) of this script, scaled by what the
+    same counters read for the plain 1 GiB copy of --calibrate-copy."""
+    import hashlib
+    import os
+    root = os.path.dirname(os.path.abspath(__file__))
+    h = hashlib.sha256()
+    for f in ("tree_attn_kernel.hpp", "plan.cpp"):
+        h.update(open(os.path.join(root, "paper_2502_13575_amd", "csrc", f), "rb").read())
+    rec = {"kernel": "tree_attn_kernel", "workload": workload,
+           "source_sha256_16": h.hexdigest()[:16],
+           "fetch_size_kib_per_launch": fetch_kib, "fetch_scale": fetch_scale,
+           "write_size_kib_per_launch": write_kib, "write_scale": write_scale,
+           "hbm_bytes_per_launch": int(round((fetch_kib * fetch_scale + write_kib * write_scale) * 1024))}
+    path = os.path.join(root, "profiles", "traffic_tree_attn_%s.json" % workload)
+    with open(path, "w") as f:
+        json.dump(rec, f, indent=1)
+    print(path, rec)
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -56,7 +77,15 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "scaling hardware byte counters when profiling)")
+    ap.add_argument("--record-traffic", nargs="+", type=float, metavar="KIB",
+                    help="no GPU work: store FETCH_SIZE and WRITE_SIZE readings (KiB per launch, "
+                         "then optionally their scales, default 2.0 and 1.0) for the roofline's "
+                         "traffic field")
     args = ap.parse_args()
+    if args.record_traffic:
+        v = args.record_traffic + [2.0, 1.0][max(0, len(args.record_traffic) - 2):]
+        record_traffic(args.config, v[0], v[1], v[2], v[3])
+        return
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); "
             "--gpus %d is not supported" % args.gpus)

@@ -152,12 +152,18 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
                                int64_t* n_rows, int32_t* n_partials);
 
 /* Planner knobs, effective from the next ets_plan.  Keys:
- *   "stream_chunk"   max tokens per work item of the streaming kernel (0 = auto)
- *   "cascade_chunk"  max tokens per work item of the shared-node kernel (0 = auto)
+ *   "stream_chunk"   max tokens per work item of a single leaf query (0 = auto)
+ *   "cascade_chunk"  max tokens per work item of a shared segment (0 = auto)
  *   "cascade_min_leaves"  a segment shared by at least this many leaf queries is
- *                    read once by the shared-node kernel; below it every leaf
- *                    streams the segment itself (default 2; 0 disables the
- *                    shared-node kernel)
+ *                    read once for all of them; below it every leaf reads the
+ *                    segment itself (default 2; 0 = never share)
+ *   "cascade_rows"   query rows (leaf queries x query heads per kv head) that one
+ *                    work item of a shared segment serves: 16, 32 or 64
+ *                    (default 64); a segment with more rows is read by several
+ *                    items
+ *   "mfma"           1 (default) = matrix-core kernel for bf16 pools with
+ *                    head_dim 128; 0 = vector-ALU kernel for every shape (each
+ *                    leaf then reads its whole chain itself)
  *   "profile"        1 = record kernel times (see ets_profile_read), 0 = off
  * Unknown key or negative value: ETS_ERR_INVALID_ARG. */
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);

@@ -118,6 +118,28 @@ def test_flat_equals_tree_and_runs_are_bitwise_reproducible():
     assert (o1 - of).abs().max().item() <= 2e-3 and (l1 - lf).abs().max().item() <= 2e-3
 
 
+@pytest.mark.parametrize("share", [False, True])
+def test_repeated_runs_bitwise_equal_on_ragged_paths(share):
+    """One node of n tokens read by 8 leaf queries, for path lengths that end in partly
+    filled steps and idle waves: every run has to give the same bits (the reference
+    score of the online softmax must not depend on timing), and they match the oracle."""
+    from workload import Tree
+    cfg = TreeConfig("one", 8, 32, 128, "bf16", 0, 0, 0, 0, 0, None, seed=5)
+    opts = {} if share else {"cascade_min_leaves": 1 << 20}
+    for n in (8, 16, 17, 33, 48, 65, 96, 250):
+        tree = Tree(np.array([-1], np.int32), np.array([0], np.int64), np.array([n], np.int32),
+                    np.zeros(8, np.int32), n)
+        k, v, q = make_values_host(cfg, tree)
+        oo, ol = oracle_full(cfg, tree, k, v, q)
+        kd, vd, qd = to_device(k), to_device(v), to_device(q)
+        with make_ctx(cfg, opts) as ctx:
+            runs = [gpu_attn(ctx, tree, kd, vd, qd) for _ in range(4)]
+        for out, lse, _ in runs[1:]:
+            assert torch.equal(out, runs[0][0]) and torch.equal(lse, runs[0][1]), "n=%d" % n
+        compare(runs[0][0].cpu().numpy().reshape(-1, 128), runs[0][1].cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "one node, n=%d" % n)
+
+
 def test_edge_cases_empty_and_duplicate_leaves():
     cfg = TreeConfig("edge", 1, 4, 128, "bf16", 0, 0, 0, 0, 0, None, seed=77)
     parent = np.array([-1, 0, -1, 2], np.int32)
