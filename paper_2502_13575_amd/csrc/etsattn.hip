@@ -29,6 +29,7 @@ struct ets_ctx {
     CascadeItem* d_cascade = nullptr;
     int32_t* d_ent_order = nullptr;
     int32_t* d_part_base = nullptr;
+    int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
     // kernel timing (benchmarks only): four events per recorded call
@@ -73,9 +74,11 @@ ets_status upload_plan(ets_ctx* c) {
     const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
     const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
-    const size_t b_ent = align_up(p.ent_order.size() * sizeof(int32_t), 256);
+    // the kernel reads up to 16 entries past an item's own with scalar loads: both
+    // per-entry tables get 16 zero entries at the end
+    const size_t b_ent = align_up((p.ent_order.size() + 16) * sizeof(int32_t), 256);
     const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
-    const size_t total = b_runs + b_stream + b_casc + b_ent + b_base + 256;
+    const size_t total = b_runs + b_stream + b_casc + 2 * b_ent + b_base + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -92,6 +95,7 @@ ets_status upload_plan(ets_ctx* c) {
         put(p.cascade_items.data(), p.cascade_items.size() * sizeof(CascadeItem), b_casc);
     const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
     const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
+    const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
 
     DeviceGuard guard(c->device);
     if (!guard.ok) return ETS_ERR_HIP;
@@ -116,6 +120,7 @@ ets_status upload_plan(ets_ctx* c) {
     c->d_cascade = reinterpret_cast<CascadeItem*>(c->d_buf + o_casc);
     c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
     c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
+    c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
     return ETS_OK;
 }
 
@@ -161,7 +166,7 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
         hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0,
                            a.stream, static_cast<const bf16_t*>(a.k),
                            static_cast<const bf16_t*>(a.v), static_cast<const bf16_t*>(a.q),
-                           c->d_runs, c->d_cascade + i0, c->d_ent_order, c->d_part_base, g_shift,
+                           c->d_runs, c->d_cascade + i0, c->d_ent_order, c->d_ent_base, g_shift,
                            c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
     }
 }

@@ -343,6 +343,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+    p.ent_base.resize((size_t)L);
+    for (int32_t i = 0; i < L; ++i) p.ent_base[i] = p.part_base[p.ent_order[i]];
     st.n_partials = p.part_base[L];
     st.n_stream_items = (int64_t)p.stream_items.size();
     st.n_cascade_items = (int64_t)p.cascade_items.size();

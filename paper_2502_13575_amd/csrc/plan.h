@@ -64,6 +64,7 @@ struct Plan {
     std::vector<CascadeItem> cascade_items;
     std::vector<int32_t> ent_order;   // leaf queries in depth-first segment order
     std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
+    std::vector<int32_t> ent_base;    // [L] part_base of ent_order[i], for the kernel's scalar loads
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
     ets_stats stats{};
 };

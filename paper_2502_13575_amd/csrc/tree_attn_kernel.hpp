@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
     const CascadeItem* __restrict__ items, const int32_t* __restrict__ ent_order,
-    const int32_t* __restrict__ part_base, int g_shift, float scale_log2e,
+    const int32_t* __restrict__ ent_base, int g_shift, float scale_log2e,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
     constexpr int D = 128;
     const int n_kv_heads = (int)gridDim.x;
@@ -281,9 +281,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // Prologue loads, in the order their results are needed (vector loads return in
     // order): the lane's query index, the first tile, the step list, then the query
     // row, which depends on the first.
+    // The leaf queries of the wave's 16 rows and their partial slots come through scalar
+    // loads (uniform addresses; both tables are padded, so entries past the item's own
+    // are readable): scalar loads do not queue behind the CU's K/V loads, and the query
+    // rows can be requested one memory round trip earlier.
     const int r_lane = 16 * blk + a;
-    const int rr = r_lane < R ? r_lane : 0;  // padding rows read a valid row; never written
-    const int ent = ent_order[it.ent_begin + (rr >> g_shift)];
+    const int e_lane = a >> g_shift;  // entry of the lane's row within the wave's block
+    const int32_t* s_ent = ent_order + it.ent_begin + ((16 * blk) >> g_shift);
+    const int32_t* s_base = ent_base + it.ent_begin + ((16 * blk) >> g_shift);
+    int32_t t_ent[16], t_base[16];  // loaded unconditionally: two wide scalar loads
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        t_ent[k] = s_ent[k];
+        t_base[k] = s_base[k];
+    }
+    int ent = t_ent[0], ent_slot = t_base[0];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) {
+        if (k < (16 >> g_shift)) {
+            ent = e_lane == k ? t_ent[k] : ent;
+            ent_slot = e_lane == k ? t_base[k] : ent_slot;
+        }
+    }
+    const int rr = r_lane;  // rows past R belong to padding entries: read, never written
 
     Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
     if (rowpar)
@@ -306,7 +326,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         const bf16_t* qp = q + ((int64_t)ent * n_q_heads + head) * D;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
-        out_row = (part_base[ent] + it.slot_off) * n_q_heads + head;
+        out_row = (ent_slot + it.slot_off) * n_q_heads + head;
     }
     if ((int)threadIdx.x < n_steps) sm_desc[threadIdx.x] = desc_raw;
 
