@@ -469,17 +469,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             oacc[x] = oacc[x] * f_own + fold[x * 64] + fold[(8 + x) * 64] + fold[(16 + x) * 64];
     }
 
-    // partial result of row a of the wave's block: lane group b holds d = 32 b + 8 i + x
-    if (r_lane < R) {
-        float* dst = ws_o + (int64_t)out_row * D + 32 * b;
+    // Partial result of the wave's block.  Lane (a, b) holds row a, d = 32 b + 8 i + x:
+    // written from there, every store instruction would touch 64 different cache lines
+    // with 16 bytes each.  The block goes through a wave-private LDS region (rows padded
+    // to 132 floats) instead, and each store instruction writes two whole 512-byte rows.
+    if (rowpar ? !computes : w != 0) return;
+    constexpr int OROW = 132;
+    float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<float4*>(dst + 8 * i) =
-                make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
-            *reinterpret_cast<float4*>(dst + 8 * i + 4) =
-                make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
-        }
-        if (b == 0) ws_ml[out_row] = make_float2(m * scale_log2e, l);
+    for (int i = 0; i < 4; ++i) {
+        float* p = ob + a * OROW + 32 * b + 8 * i;
+        *reinterpret_cast<float4*>(p) = make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
+        *reinterpret_cast<float4*>(p + 4) =
+            make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
+    }
+    if (b == 0 && r_lane < R) ws_ml[out_row] = make_float2(m * scale_log2e, l);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int col = (lane & 31) * 4;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int r = 2 * k + (lane >> 5);                   // row of the block this lane stores
+        const int32_t row_out = __shfl(out_row, r, 64);      // lane r holds row r (a = r, b = 0)
+        const float4 v = *reinterpret_cast<const float4*>(ob + r * OROW + col);
+        if (16 * blk + r < R) *reinterpret_cast<float4*>(ws_o + (int64_t)row_out * D + col) = v;
     }
 }
 
