@@ -289,7 +289,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
                 if (use_mfma) {
                     p.cascade_items.push_back(CascadeItem{c.run_begin, c.run_end, ent_pos[l], 1,
-                                                          shared_slots + c_idx, c.tokens, 0, 0});
+                                                          shared_slots + c_idx, c.tokens, 1, 0});
                     cascade_cost.push_back(ceil_div(c.tokens, kTile) * t_mem);
                     p.max_cascade_ent = std::max(p.max_cascade_ent, 1);
                 } else {
@@ -313,7 +313,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 const int32_t ne = (int32_t)std::min<int64_t>(ent_per_item, sg.cnt - e0);
                 p.cascade_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
                                                       sg.ent_begin + (int32_t)e0, ne,
-                                                      sg.prefix + c, ch.tokens, 0, 0});
+                                                      sg.prefix + c, ch.tokens,
+                                                      sg.cnt <= ent_per_item ? 1 : 0, 0});
                 cascade_cost.push_back(ceil_div(ch.tokens, kTile) * tile_cost((int64_t)ne * G));
                 p.max_cascade_ent = std::max(p.max_cascade_ent, ne);
             }

@@ -39,7 +39,7 @@ struct CascadeItem {
     int32_t n_ent;
     int32_t slot_off;
     int32_t n_tokens;
-    int32_t pad0;
+    int32_t sole_reader;  // 1: no other item reads these rows
     int32_t pad1;
 };
 

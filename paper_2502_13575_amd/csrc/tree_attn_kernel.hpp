@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int rr = r_lane;  // rows past R belong to padding entries: read, never written
 
     Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
-    if (rowpar)
+    if (rowpar && !it.sole_reader)
         issue_loads(sd_loaded, std::integral_constant<int, 0>{});
     else
         issue_loads(sd_loaded, std::integral_constant<int, 2>{});
@@ -379,9 +379,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();  // step list and first tile are in LDS
 
+        // rows that no other item reads (a segment whose queries fit one item) are
+        // fetched non-temporally; rows that further row groups re-read stay in L2
+        auto tile_loop = [&](auto aux_tag) {
         for (int tile = 0; tile < n_tiles; ++tile) {
             sd_loaded = read_desc(2 * (tile + 1) + sw);  // a step past the end has n = 0
-            issue_loads(sd_loaded, std::integral_constant<int, 0>{});
+            issue_loads(sd_loaded, aux_tag);
 
             if (computes) {
 #pragma unroll
@@ -398,6 +401,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             stage(sd_loaded);
             __syncthreads();
         }
+        };
+        if (it.sole_reader)
+            tile_loop(std::integral_constant<int, 2>{});
+        else
+            tile_loop(std::integral_constant<int, 0>{});
         if (!computes) return;
     } else {
         // Token parallel: every wave walks its own 16-token units (half hw of step
