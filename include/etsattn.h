@@ -161,6 +161,9 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
  *                    work item of a shared segment serves: 16, 32 or 64
  *                    (default 64); a segment with more rows is read by several
  *                    items
+ *   "wave_items"     a work item of at most 16 query rows and at most this many
+ *                    tokens is walked by a single wavefront, four such items to
+ *                    a workgroup (default 512; 0 = every item gets a workgroup)
  *   "mfma"           1 (default) = matrix-core kernel for bf16 pools with
  *                    head_dim 128; 0 = vector-ALU kernel for every shape (each
  *                    leaf then reads its whole chain itself)

@@ -160,13 +160,17 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     if (n_items <= 0) return;
     const int g = c->shape.n_q_heads / c->shape.n_kv_heads;
     const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
-    // grid: x = kv head, y = work item (at most 65535 per launch)
-    for (int64_t i0 = 0; i0 < n_items; i0 += 65535) {
-        const unsigned ny = (unsigned)std::min<int64_t>(65535, n_items - i0);
+    // grid: x = kv head, y = workgroup (at most 65535 per launch): first the items that
+    // take a workgroup each, then the small ones, four to a workgroup
+    const int64_t n_single = c->plan.n_single;
+    const int64_t n_wgs = n_single + (n_items - n_single + 3) / 4;
+    for (int64_t y0 = 0; y0 < n_wgs; y0 += 65535) {
+        const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
         hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0,
                            a.stream, static_cast<const bf16_t*>(a.k),
                            static_cast<const bf16_t*>(a.v), static_cast<const bf16_t*>(a.q),
-                           c->d_runs, c->d_cascade + i0, c->d_ent_order, c->d_ent_base, g_shift,
+                           c->d_runs, c->d_cascade, (int)y0, (int)n_single, (int)n_items,
+                           c->d_ent_order, c->d_ent_base, g_shift,
                            c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
     }
 }
@@ -266,7 +270,8 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
     else if (!std::strcmp(key, "cascade_rows")) {
         if (value != 16 && value != 32 && value != 64) return ETS_ERR_INVALID_ARG;
         ctx->opt.cascade_rows = value;
-    } else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
+    } else if (!std::strcmp(key, "wave_items")) ctx->opt.wave_items = value;
+    else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
     else if (!std::strcmp(key, "profile")) {
         if (value != 0 && ctx->device < 0) return ETS_ERR_HIP;
         ctx->profile = value != 0;

@@ -338,8 +338,22 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
             return cascade_cost[a] > cascade_cost[b];
         });
-        std::vector<CascadeItem> sorted(idx.size());
-        for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.cascade_items[idx[i]];
+        // Small items with at most 16 query rows follow the others (both groups longest
+        // first): one wave walks such an item alone, four of them share a workgroup,
+        // which divides the number of short workgroups the device has to start by four.
+        std::vector<CascadeItem> sorted;
+        sorted.reserve(idx.size());
+        // A lone wave needs about 2.5 us per 16-token unit; such an item should not
+        // last longer than a quarter of the time the whole call is expected to take.
+        const int64_t wave_cap = std::min<int64_t>(opt.wave_items, hbm_ns / 4 / 2500 * 16);
+        auto small = [&](const CascadeItem& it) {
+            return (int64_t)it.n_ent * G <= 16 && it.n_tokens <= wave_cap;
+        };
+        for (size_t i = 0; i < idx.size(); ++i)
+            if (!small(p.cascade_items[idx[i]])) sorted.push_back(p.cascade_items[idx[i]]);
+        p.n_single = (int32_t)sorted.size();
+        for (size_t i = 0; i < idx.size(); ++i)
+            if (small(p.cascade_items[idx[i]])) sorted.push_back(p.cascade_items[idx[i]]);
         p.cascade_items.swap(sorted);
     }
 

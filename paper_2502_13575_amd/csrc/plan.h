@@ -47,6 +47,8 @@ struct PlanOptions {
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
     int64_t cascade_rows = 64;       // query rows per shared work item (16, 32 or 64)
+    int64_t wave_items = 512;        // an item of <= 16 rows and at most this many tokens is
+                                     // walked by one wave, four such items to a workgroup (0 = off)
     int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
 };
@@ -66,6 +68,8 @@ struct Plan {
     std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
     std::vector<int32_t> ent_base;    // [L] part_base of ent_order[i], for the kernel's scalar loads
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
+    int32_t n_single = 0;             // cascade_items[0, n_single): one workgroup each; the rest:
+                                      // small items, four to a workgroup (one wave each)
     ets_stats stats{};
 };
 

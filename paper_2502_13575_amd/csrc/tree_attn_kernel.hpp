@@ -194,8 +194,9 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
-    const CascadeItem* __restrict__ items, const int32_t* __restrict__ ent_order,
-    const int32_t* __restrict__ ent_base, int g_shift, float scale_log2e,
+    const CascadeItem* __restrict__ items, int wg_base, int n_single, int n_items,
+    const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
+    float scale_log2e,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
     constexpr int D = 128;
     const int n_kv_heads = (int)gridDim.x;
@@ -218,7 +219,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int a = lane & 15;  // 16-byte piece of a row when loading; MFMA row/column index
     const int b = lane >> 4;  // token sub-index when loading; MFMA contraction group kg
     const int h = blockIdx.x;  // kv head; consecutive workgroups share an item
-    const CascadeItem it = items[blockIdx.y];
+    // workgroups [0, n_single) take one item each; the others hold four small items,
+    // one per wave, which then works alone: no barrier below this point on that path
+    const int wg = wg_base + (int)blockIdx.y;
+    const bool wave_item = wg >= n_single;
+    const int item_idx = wave_item ? n_single + 4 * (wg - n_single) + w : wg;
+    if (item_idx >= n_items) return;
+    const CascadeItem it = items[item_idx];
     const int G = 1 << g_shift;
     const int n_q_heads = n_kv_heads << g_shift;
     const int R = it.n_ent << g_shift;
@@ -304,6 +311,118 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         }
     }
     const int rr = r_lane;  // rows past R belong to padding entries: read, never written
+
+    // Partial result of the wave's block.  Lane (a, b) holds row a, d = 32 b + 8 i + x:
+    // written from there, every store instruction would touch 64 different cache lines
+    // with 16 bytes each.  The block goes through a wave-private LDS region (rows padded
+    // to 132 floats) instead, and each store instruction writes two whole 512-byte rows.
+    auto store_partial = [&](const f32x4_t (&oacc)[8], float m, float l, int32_t out_row) {
+        constexpr int OROW = 132;
+        float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float* p = ob + a * OROW + 32 * b + 8 * i;
+            *reinterpret_cast<float4*>(p) =
+                make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
+            *reinterpret_cast<float4*>(p + 4) =
+                make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
+        }
+        if (b == 0 && r_lane < R) ws_ml[out_row] = make_float2(m * scale_log2e, l);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int col = (lane & 31) * 4;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int r = 2 * k + (lane >> 5);               // row of the block this lane stores
+            const int32_t row_out = __shfl(out_row, r, 64);  // lane r holds row r (a = r, b = 0)
+            const float4 v = *reinterpret_cast<const float4*>(ob + r * OROW + col);
+            if (16 * blk + r < R) *reinterpret_cast<float4*>(ws_o + (int64_t)row_out * D + col) = v;
+        }
+    };
+
+    if (wave_item) {
+        // ---- A small item walked by this wave alone: 16-token units in order (unit u =
+        // half u & 1 of step u >> 1) through the wave's own LDS region, next unit's loads
+        // in flight while the current one is computed; no fold, no workgroup barrier.
+        const uint32_t k_off0 = (uint32_t)b * stride_b + a * 16;        // K row b (+ 4 i)
+        const uint32_t v_off0 = (uint32_t)(4 * b) * stride_b + a * 16;  // V row 4 b (+ i)
+        u32x4_t* ksw = smem + w * (16 * KROW + 256);
+        u32x2_t* vsw = reinterpret_cast<u32x2_t*>(ksw + 16 * KROW);
+        auto unit_rows = [&](int u, int64_t& tok) {
+            const Run sd = my_steps[u >> 1];  // uniform: scalar load
+            tok = sd.tok + 16 * (u & 1);
+            return min(16, max(0, sd.n - 16 * (u & 1)));
+        };
+        auto issue_unit = [&](int64_t tok, int n) {
+            if (n > 0) {
+                const int64_t base = (tok * n_kv_heads + h) * (int64_t)D * 2;
+                char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;
+                char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
+                const __amdgpu_buffer_rsrc_t kr =
+                    __builtin_amdgcn_make_buffer_rsrc(kb, 0, n * (int)stride_b, 0x00020000);
+                const __amdgpu_buffer_rsrc_t vr =
+                    __builtin_amdgcn_make_buffer_rsrc(vb, 0, n * (int)stride_b, 0x00020000);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    kraw[i] = __builtin_bit_cast(
+                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                     kr, k_off0 + (uint32_t)(4 * i) * stride_b, 0, 2));
+                    vraw[i] = __builtin_bit_cast(
+                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                     vr, v_off0 + (uint32_t)i * stride_b, 0, 2));
+                }
+            }
+        };
+        auto stage_own = [&](int n) {
+            if (n > 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = kraw[i];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+                    u32x2_t t;
+                    t[0] = __builtin_amdgcn_perm(vraw[1][x >> 1], vraw[0][x >> 1], sel);
+                    t[1] = __builtin_amdgcn_perm(vraw[3][x >> 1], vraw[2][x >> 1], sel);
+                    vsw[x * 64 + lane] = t;
+                }
+            }
+        };
+        const int n_units = 2 * n_steps;
+        int64_t tok = 0;
+        int n_cur = n_units > 0 ? unit_rows(0, tok) : 0;
+        issue_unit(tok, n_cur);
+        const int head = h * G + (rr & (G - 1));
+        const bf16_t* qp = q + ((int64_t)ent * n_q_heads + head) * D;
+        bf16x8_t qf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
+        const int32_t out_row = (ent_slot + it.slot_off) * n_q_heads + head;
+        f32x4_t oacc[8];
+        float m = -INFINITY, lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) oacc[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        stage_own(n_cur);
+        __builtin_amdgcn_s_waitcnt(0);  // nothing issued so far may count against the loop's waits
+        for (int u = 0; u < n_units; ++u) {
+            int64_t tok_next = 0;
+            const int n_next = u + 1 < n_units ? unit_rows(u + 1, tok_next) : 0;
+            issue_unit(tok_next, n_next);
+            if (n_cur > 0)
+                attn_half_step(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
+                               scale_log2e, raise_margin);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            stage_own(n_next);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            n_cur = n_next;
+        }
+        float l = lsum;
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        store_partial(oacc, m, l, out_row);
+        return;
+    }
 
     Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
     if (rowpar && !it.sole_reader)
@@ -477,31 +596,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             oacc[x] = oacc[x] * f_own + fold[x * 64] + fold[(8 + x) * 64] + fold[(16 + x) * 64];
     }
 
-    // Partial result of the wave's block.  Lane (a, b) holds row a, d = 32 b + 8 i + x:
-    // written from there, every store instruction would touch 64 different cache lines
-    // with 16 bytes each.  The block goes through a wave-private LDS region (rows padded
-    // to 132 floats) instead, and each store instruction writes two whole 512-byte rows.
     if (rowpar ? !computes : w != 0) return;
-    constexpr int OROW = 132;
-    float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float* p = ob + a * OROW + 32 * b + 8 * i;
-        *reinterpret_cast<float4*>(p) = make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
-        *reinterpret_cast<float4*>(p + 4) =
-            make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
-    }
-    if (b == 0 && r_lane < R) ws_ml[out_row] = make_float2(m * scale_log2e, l);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    const int col = (lane & 31) * 4;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int r = 2 * k + (lane >> 5);                   // row of the block this lane stores
-        const int32_t row_out = __shfl(out_row, r, 64);      // lane r holds row r (a = r, b = 0)
-        const float4 v = *reinterpret_cast<const float4*>(ob + r * OROW + col);
-        if (16 * blk + r < R) *reinterpret_cast<float4*>(ws_o + (int64_t)row_out * D + col) = v;
-    }
+    store_partial(oacc, m, l, out_row);
 }
 
 }  // namespace ets

@@ -18,6 +18,7 @@ pytestmark = pytest.mark.gpu
 VARIANTS = {
     "tree": (ets.ETS_PLAN_TREE, {}),
     "tree_no_sharing": (ets.ETS_PLAN_TREE, {"cascade_min_leaves": 0}),
+    "tree_workgroup_items": (ets.ETS_PLAN_TREE, {"wave_items": 0}),
     "tree_valu_only": (ets.ETS_PLAN_TREE, {"mfma": 0}),
     "flat": (ets.ETS_PLAN_FLAT, {}),
 }
@@ -95,7 +96,8 @@ def test_fuzz_irregular_forests(seed):
     cfg = TreeConfig("fuzz", hkv, hq, d, dt, 0, 0, 0, 0, 0, None, seed=900 + seed)
     tree = random_tree(seed, n_nodes=50, n_leaves=21, max_tokens=90)
     options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3],
-               "cascade_rows": [64, 16, 32][(seed // 2) % 3]}
+               "cascade_rows": [64, 16, 32][(seed // 2) % 3],
+               "wave_items": [512, 0, 48, 100000][seed % 4]}
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
