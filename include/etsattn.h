@@ -151,6 +151,35 @@ ets_status ets_plan_leaf_counts(const ets_ctx* ctx, int64_t* leaf_count);
 ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, int64_t cap,
                                int64_t* n_rows, int32_t* n_partials);
 
+/* Decode-step advance.  Between two decode tokens of one search step the tree's
+ * topology is fixed and only the nodes that hold leaf queries grow, by one token each
+ * (ETS paper, Sec. 4.1: the tree changes once per step; App. B: leaves are the latest
+ * steps).  Per decode token the caller runs, on one stream and in this order:
+ * ets_kv_append, ets_plan_advance, then ets_tree_decode_attn for every layer (a layer's
+ * append may also directly precede that layer's attention call, with the advance first).
+ *
+ * ets_kv_append writes, for every distinct node of leaf_node, one new row of K and V
+ * at pool row tok_offset[node] + n_tokens[node] (the plan's current lengths), which
+ * the caller must have reserved for that node.
+ *   k_pool, v_pool  DEVICE, as in ets_tree_decode_attn, written
+ *   pool_tokens     rows in each pool; must exceed every written row, else
+ *                   ETS_ERR_INVALID_ARG and nothing is written
+ *   k_new, v_new    DEVICE, [n_leaves][n_kv_heads][head_dim] of shape.dtype, 16-byte
+ *                   aligned: row l is the new token of leaf query l; when several leaf
+ *                   queries sit on one node, the first of them supplies the row
+ * Asynchronous on hip_stream; no allocation.
+ *
+ * ets_plan_advance makes every distinct node of leaf_node one token longer in the plan
+ * (the library's copy of the tree, statistics, and the step lists on the device, the
+ * latter through a small kernel on hip_stream).  The step lists have room for at
+ * least 32 advances; when it is used up the call plans again from its grown copy of
+ * the tree (this waits for the context's previous work, like ets_plan) and sets
+ * *replanned (may be NULL) to 1: n_partials and workspace_bytes may then have changed
+ * and are to be read again with ets_plan_stats.  Works without a device too. */
+ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_tokens,
+                         const void* k_new, const void* v_new, void* hip_stream);
+ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned);
+
 /* Planner knobs, effective from the next ets_plan.  Keys:
  *   "stream_chunk"   max tokens per work item of a single leaf query (0 = auto)
  *   "cascade_chunk"  max tokens per work item of a shared segment (0 = auto)

@@ -204,3 +204,24 @@ def merge(o, m, l):
     _load().ets_oracle_merge(d, n, _p(o, C.c_double), _p(m, C.c_double), _p(l, C.c_double),
                              _p(out, C.c_double), C.byref(lse))
     return out, lse.value
+
+
+def append_kv(tok_offset, n_tokens, leaf_node, k_pool, v_pool, k_new, v_new):
+    """Decode-step advance, written out (ETS paper Sec. 4.1: within a search step the
+    topology is fixed; App. B: the leaves are the latest steps, which are the ones being
+    generated).  Every distinct node of `leaf_node` receives one token: the K and V row
+    of the first leaf query that sits on it goes to pool row tok_offset + n_tokens of
+    that node, and the node becomes one token longer.  Pools are modified in place;
+    returns the new n_tokens array."""
+    n_tokens = np.array(n_tokens, dtype=np.int32, copy=True)
+    seen = set()
+    for l, n in enumerate(np.asarray(leaf_node).tolist()):
+        if n in seen:
+            continue
+        seen.add(n)
+        row = int(tok_offset[n]) + int(n_tokens[n])
+        k_pool[row] = k_new[l]
+        v_pool[row] = v_new[l]
+    for n in seen:
+        n_tokens[n] += 1
+    return n_tokens

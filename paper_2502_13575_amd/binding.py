@@ -82,6 +82,10 @@ def load_library():
     lib.ets_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
     lib.ets_tree_decode_attn.restype = C.c_int
     lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
+    lib.ets_kv_append.restype = C.c_int
+    lib.ets_kv_append.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
+    lib.ets_plan_advance.restype = C.c_int
+    lib.ets_plan_advance.argtypes = [vp, vp, i32p]
     lib.ets_profile_read.restype = C.c_int
     lib.ets_profile_read.argtypes = [vp, C.POINTER(EtsProfile)]
     lib.ets_strerror.restype = C.c_char_p
@@ -190,6 +194,20 @@ def ets_tree_decode_attn(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse, wor
         "ets_tree_decode_attn")
 
 
+def ets_kv_append(ctx, k_pool, v_pool, pool_tokens: int, k_new, v_new, stream=None) -> None:
+    st = None if stream is None else C.c_void_p(int(stream))
+    _check(load_library().ets_kv_append(ctx, _dev_ptr(k_pool), _dev_ptr(v_pool), int(pool_tokens),
+                                        _dev_ptr(k_new), _dev_ptr(v_new), st), "ets_kv_append")
+
+
+def ets_plan_advance(ctx, stream=None) -> bool:
+    """Returns True when the library had to plan again (read the statistics again then)."""
+    flag = C.c_int32(0)
+    st = None if stream is None else C.c_void_p(int(stream))
+    _check(load_library().ets_plan_advance(ctx, st, C.byref(flag)), "ets_plan_advance")
+    return bool(flag.value)
+
+
 def ets_profile_read(ctx) -> EtsProfile:
     pr = EtsProfile()
     _check(load_library().ets_profile_read(ctx, C.byref(pr)), "ets_profile_read")
@@ -239,6 +257,12 @@ class Context:
 
     def leaf_cover(self, leaf):
         return ets_plan_leaf_cover(self._ctx, leaf)
+
+    def kv_append(self, k_pool, v_pool, pool_tokens, k_new, v_new, stream=None):
+        ets_kv_append(self._ctx, k_pool, v_pool, pool_tokens, k_new, v_new, stream)
+
+    def plan_advance(self, stream=None) -> bool:
+        return ets_plan_advance(self._ctx, stream)
 
     def profile_read(self) -> EtsProfile:
         return ets_profile_read(self._ctx)

@@ -1,0 +1,52 @@
+// Decode-step advance on the device: between two tokens of one search step the tree's
+// topology is fixed (ETS paper, Sec. 4.1) and only the nodes that hold leaf queries grow.
+//   advance_runs_kernel  extends, in the step lists the attention kernels read, the tail
+//                        of every copy of every growing node by one row;
+//   kv_append_kernel     writes the new token's K and V row of every growing node into
+//                        the pools.
+#pragma once
+
+#include "device_utils.hpp"
+#include "plan.h"
+
+namespace ets {
+
+// One thread per AdvEntry.  `advances` = advances already applied since the plan was built.
+__global__ void advance_runs_kernel(Run* __restrict__ runs, const AdvEntry* __restrict__ adv,
+                                    int n_adv, int piece, int advances) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_adv) return;
+    const AdvEntry e = adv[i];
+    Run* last = runs + e.r_last;
+    if (e.mergeable && (piece == 0 || last->n < piece)) {
+        last->n += 1;
+    } else {
+        Run* spare = runs + e.r_spare;
+        if (spare->n == 0) spare->tok = e.end0 + advances;
+        spare->n += 1;
+    }
+}
+
+// One workgroup per growing node: row_bytes = n_kv_heads * head_dim * element size
+// (a multiple of 16) of K and of V go from row src[node] of k_new / v_new to pool row
+// row0[node] + advances.
+__global__ __launch_bounds__(256) void kv_append_kernel(char* __restrict__ k_pool,
+                                                        char* __restrict__ v_pool,
+                                                        const char* __restrict__ k_new,
+                                                        const char* __restrict__ v_new,
+                                                        const int32_t* __restrict__ src,
+                                                        const int64_t* __restrict__ row0,
+                                                        int advances, int row_bytes) {
+    const int node = blockIdx.x;
+    const int64_t dst = (row0[node] + advances) * (int64_t)row_bytes;
+    const int64_t from = (int64_t)src[node] * row_bytes;
+    const int pieces = row_bytes / 16;
+    for (int i = threadIdx.x; i < 2 * pieces; i += blockDim.x) {
+        const bool is_v = i >= pieces;
+        const int off = (is_v ? i - pieces : i) * 16;
+        const uint4 val = *reinterpret_cast<const uint4*>((is_v ? v_new : k_new) + from + off);
+        *reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + dst + off) = val;
+    }
+}
+
+}  // namespace ets

@@ -7,6 +7,7 @@
 #include <new>
 #include <vector>
 
+#include "advance_kernel.hpp"
 #include "etsattn.h"
 #include "merge_kernel.hpp"
 #include "plan.h"
@@ -30,6 +31,9 @@ struct ets_ctx {
     int32_t* d_ent_order = nullptr;
     int32_t* d_part_base = nullptr;
     int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
+    AdvEntry* d_adv = nullptr;       // decode-step advance: tails to extend
+    int32_t* d_adv_src = nullptr;    // per growing node: leaf query that supplies its new token
+    int64_t* d_adv_row0 = nullptr;   // per growing node: first free pool row at plan time
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
     // kernel timing (benchmarks only): four events per recorded call
@@ -78,7 +82,11 @@ ets_status upload_plan(ets_ctx* c) {
     // per-entry tables get 16 zero entries at the end
     const size_t b_ent = align_up((p.ent_order.size() + 16) * sizeof(int32_t), 256);
     const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
-    const size_t total = b_runs + b_stream + b_casc + 2 * b_ent + b_base + 256;
+    const size_t b_adv = align_up(p.adv.size() * sizeof(AdvEntry), 256);
+    const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
+    const size_t b_arow = align_up(p.adv_row0.size() * sizeof(int64_t), 256);
+    const size_t total =
+        b_runs + b_stream + b_casc + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -96,6 +104,9 @@ ets_status upload_plan(ets_ctx* c) {
     const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
     const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
     const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
+    const size_t o_adv = put(p.adv.data(), p.adv.size() * sizeof(AdvEntry), b_adv);
+    const size_t o_asrc = put(p.adv_src.data(), p.adv_src.size() * sizeof(int32_t), b_asrc);
+    const size_t o_arow = put(p.adv_row0.data(), p.adv_row0.size() * sizeof(int64_t), b_arow);
 
     DeviceGuard guard(c->device);
     if (!guard.ok) return ETS_ERR_HIP;
@@ -121,6 +132,9 @@ ets_status upload_plan(ets_ctx* c) {
     c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
     c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
     c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
+    c->d_adv = reinterpret_cast<AdvEntry*>(c->d_buf + o_adv);
+    c->d_adv_src = reinterpret_cast<int32_t*>(c->d_buf + o_asrc);
+    c->d_adv_row0 = reinterpret_cast<int64_t*>(c->d_buf + o_arow);
     return ETS_OK;
 }
 
@@ -289,6 +303,76 @@ ets_status ets_plan(ets_ctx* ctx, const ets_tree* tree, int mode) {
         if (s != ETS_OK) ctx->plan.valid = false;
     }
     return s;
+}
+
+ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    if (replanned) *replanned = 0;
+    Plan& p = ctx->plan;
+    const int advances_before = p.advances;
+    if (advance_in_place(p)) {
+        if (ctx->device >= 0 && !p.adv.empty()) {
+            DeviceGuard guard(ctx->device);
+            if (!guard.ok) return ETS_ERR_HIP;
+            hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+            const int n = (int)p.adv.size();
+            hipLaunchKernelGGL(advance_runs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                               stream, ctx->d_runs, ctx->d_adv, n, (int)p.piece, advances_before);
+            if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+            ctx->last_stream = stream;
+            ctx->stream_used = true;
+        }
+        return ETS_OK;
+    }
+    // no room left in the step lists: plan again from the grown copy of the tree
+    try {
+        advance_tree(p);
+        const std::vector<int32_t> parent = p.parent, n_tokens = p.n_tokens, leaf_node = p.leaf_node;
+        const std::vector<int64_t> tok_offset = p.tok_offset;
+        const ets_tree t{(int32_t)parent.size(), parent.data(),        tok_offset.data(),
+                         n_tokens.data(),        (int32_t)leaf_node.size(), leaf_node.data()};
+        ets_status s = build_plan(ctx->shape, ctx->opt, t, p.mode, p);
+        if (s != ETS_OK) return s;
+        if (ctx->device >= 0) {
+            s = upload_plan(ctx);
+            if (s != ETS_OK) {
+                p.valid = false;
+                return s;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        p.valid = false;
+        return ETS_ERR_NOMEM;
+    }
+    if (replanned) *replanned = 1;
+    return ETS_OK;
+}
+
+ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_tokens,
+                         const void* k_new, const void* v_new, void* hip_stream) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    const Plan& p = ctx->plan;
+    const int n = (int)p.adv_node.size();
+    if (n == 0) return ETS_OK;
+    if (!k_pool || !v_pool || !k_new || !v_new) return ETS_ERR_INVALID_ARG;
+    // every node's next row has to exist in the pool
+    if (pool_tokens < p.stats.min_pool_tokens + 1) return ETS_ERR_INVALID_ARG;
+    const int64_t esz = ctx->shape.dtype == ETS_F32 ? 4 : 2;
+    const int row_bytes = (int)(ctx->shape.n_kv_heads * (int64_t)ctx->shape.head_dim * esz);
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)n), dim3(256), 0, stream,
+                       static_cast<char*>(k_pool), static_cast<char*>(v_pool),
+                       static_cast<const char*>(k_new), static_cast<const char*>(v_new),
+                       ctx->d_adv_src, ctx->d_adv_row0, (int)p.advances, row_bytes);
+    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    ctx->last_stream = stream;
+    ctx->stream_used = true;
+    return ETS_OK;
 }
 
 ets_status ets_plan_stats(const ets_ctx* ctx, ets_stats* out) {

@@ -36,29 +36,45 @@ constexpr int64_t kMaxPiecesPerChunk = 256;  // step list the matrix-core kernel
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
 
-// Appends the (merged) pool runs of a node list to `out`.
-void collect_runs(const Plan& p, const std::vector<int32_t>& nodes, std::vector<Run>& out) {
+// Appends the (merged) pool runs of a node list to `out`.  A node that holds leaf
+// queries grows by a token per decode step: the run that ends such a node is marked
+// (pad = 1) and nothing is merged behind it.  Returns false if a growing node has no
+// rows yet (there is no run to mark).
+bool collect_runs(const Plan& p, const std::vector<int32_t>& nodes, const std::vector<int64_t>& own,
+                  std::vector<Run>& out) {
+    bool ok = true;
+    bool closed = true;  // the previous run must not be extended
     for (int32_t n : nodes) {
         const int32_t len = p.n_tokens[n];
-        if (len <= 0) continue;
+        const bool grows = own[n] > 0;
+        if (len <= 0) {
+            if (grows) ok = false;
+            continue;
+        }
         const int64_t tok = p.tok_offset[n];
-        if (!out.empty() && out.back().tok + out.back().n == tok &&
+        if (!closed && !out.empty() && out.back().tok + out.back().n == tok &&
             (int64_t)out.back().n + len <= std::numeric_limits<int32_t>::max()) {
             out.back().n += len;
         } else {
             out.push_back(Run{tok, len, 0});
         }
+        out.back().pad = grows ? 1 : 0;
+        closed = grows;
     }
+    return ok;
 }
 
 // Cuts `src` (total `tokens` rows) into chunks of at most `cap` rows, sized
 // evenly in multiples of 32 rows, appending the chunks' runs to plan.runs.  With
 // piece > 0 no emitted run is longer than `piece` rows (the matrix-core kernel
-// walks its run list in steps of at most 32 rows).
-void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap, int64_t piece,
+// walks its run list in steps of at most 32 rows).  Behind the last piece of a marked
+// run (a growing node's tail) an empty spare run is emitted and an AdvEntry recorded;
+// returns false if a chunk's step list had no room for a spare.
+bool cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap, int64_t piece,
               std::vector<Chunk>& chunks) {
     chunks.clear();
-    if (tokens <= 0) return;
+    if (tokens <= 0) return true;
+    bool ok = true;
     cap = std::max<int64_t>(cap, 32);
     int64_t n_chunks = ceil_div(tokens, cap);
     int64_t per = std::min(cap, round_up(ceil_div(tokens, n_chunks), 32));
@@ -79,6 +95,17 @@ void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
             c.tokens += (int32_t)take;
             ++pieces;
             if (used == src[ri].n) {
+                if (src[ri].pad) {
+                    if (piece > 0 && pieces >= kMaxPiecesPerChunk) {
+                        ok = false;
+                    } else {
+                        const int32_t r_last = (int32_t)p.runs.size() - 1;
+                        const int64_t end0 = src[ri].tok + src[ri].n;
+                        p.adv.push_back(AdvEntry{r_last, r_last + 1, end0, 1, 0});
+                        p.runs.push_back(Run{end0, 0, 0});
+                        ++pieces;
+                    }
+                }
                 ++ri;
                 used = 0;
             }
@@ -87,6 +114,7 @@ void cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
         left -= c.tokens;
         chunks.push_back(c);
     }
+    return ok;
 }
 
 ets_status validate(const ets_tree& t) {
@@ -167,6 +195,9 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     p.ent_order.assign(L, 0);
     p.part_base.assign((size_t)L + 1, 0);
     p.max_cascade_ent = 0;
+    p.adv.clear();
+    p.adv_in_place = true;
+    p.advances = 0;
 
     std::vector<Run> tmp_runs;
     std::vector<Chunk> chunks;
@@ -205,6 +236,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     const bool use_mfma = opt.mfma != 0 && shape.dtype == ETS_BF16 && shape.head_dim == 128;
     const bool cascade_ok = mode == ETS_PLAN_TREE && use_mfma && opt.cascade_min_leaves > 0;
     const int64_t piece = use_mfma ? 32 : 0;
+    p.piece = (int32_t)piece;
+    auto grow_end_of = [&](int32_t node) { return p.tok_offset[node] + p.n_tokens[node]; };
     const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
     const int64_t ent_per_item = std::max<int64_t>(1, opt.cascade_rows / G);
     // cost model in nanoseconds per tile of 64 tokens: a workgroup needs about
@@ -255,8 +288,9 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         if (ccap <= 0)
             ccap = item_budget_ns / tile_cost(std::min(ent_per_item, sg.cnt) * G) * kTile;
         tmp_runs.clear();
-        collect_runs(p, sg.nodes, tmp_runs);
-        cut_runs(p, tmp_runs, sg.tokens, ccap, piece, seg_chunks[s]);
+        if (!collect_runs(p, sg.nodes, own, tmp_runs)) p.adv_in_place = false;
+        if (!cut_runs(p, tmp_runs, sg.tokens, ccap, piece, seg_chunks[s]))
+            p.adv_in_place = false;
         sg.n_chunks = (int32_t)seg_chunks[s].size();
     }
 
@@ -280,10 +314,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                 own_nodes.insert(own_nodes.end(), segs[seg_chain[i]].nodes.begin(),
                                  segs[seg_chain[i]].nodes.end());
             tmp_runs.clear();
-            collect_runs(p, own_nodes, tmp_runs);
+            if (!collect_runs(p, own_nodes, own, tmp_runs)) p.adv_in_place = false;
             int64_t tokens = 0;
             for (const Run& r : tmp_runs) tokens += r.n;
-            cut_runs(p, tmp_runs, tokens, scap, piece, chunks);
+            if (!cut_runs(p, tmp_runs, tokens, scap, piece, chunks)) p.adv_in_place = false;
             int32_t c_idx = 0;
             for (const Chunk& c : chunks) {
                 if (slot >= std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
@@ -358,6 +392,21 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+    {
+        std::vector<int32_t> first(N, -1);
+        p.adv_node.clear();
+        p.adv_src.clear();
+        p.adv_row0.clear();
+        for (int32_t l = 0; l < L; ++l) {
+            const int32_t n = p.leaf_node[l];
+            if (first[n] >= 0) continue;
+            first[n] = l;
+            p.adv_node.push_back(n);
+            p.adv_src.push_back(l);
+            p.adv_row0.push_back(grow_end_of(n));
+        }
+        p.adv_room = piece > 0 ? 32 : std::numeric_limits<int32_t>::max();
+    }
     p.ent_base.resize((size_t)L);
     for (int32_t i = 0; i < L; ++i) p.ent_base[i] = p.part_base[p.ent_order[i]];
     st.n_partials = p.part_base[L];
@@ -369,6 +418,40 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
 }
 
 }  // namespace
+
+void advance_tree(Plan& plan) {
+    ets_stats& st = plan.stats;
+    const int64_t tok_bytes = st.unique_tokens > 0 ? st.unique_kv_bytes / st.unique_tokens : 0;
+    for (int32_t n : plan.adv_node) {
+        plan.n_tokens[n] += 1;
+        st.unique_tokens += 1;
+        st.flat_tokens += plan.leaf_count[n];
+        st.min_pool_tokens =
+            std::max(st.min_pool_tokens, plan.tok_offset[n] + (int64_t)plan.n_tokens[n]);
+    }
+    if (tok_bytes > 0) {
+        st.unique_kv_bytes = st.unique_tokens * tok_bytes;
+        st.flat_kv_bytes = st.flat_tokens * tok_bytes;
+    }
+}
+
+bool advance_in_place(Plan& plan) {
+    if (!plan.valid || !plan.adv_in_place || plan.adv_room <= 0) return false;
+    for (const AdvEntry& e : plan.adv) {
+        Run& last = plan.runs[e.r_last];
+        if (e.mergeable && (plan.piece == 0 || last.n < plan.piece)) {
+            last.n += 1;
+        } else {
+            Run& spare = plan.runs[e.r_spare];
+            if (spare.n == 0) spare.tok = e.end0 + plan.advances;
+            spare.n += 1;
+        }
+    }
+    plan.advances += 1;
+    plan.adv_room -= 1;
+    advance_tree(plan);
+    return true;
+}
 
 void chain_of(const Plan& plan, int32_t leaf, std::vector<int32_t>& out) {
     const size_t first = out.size();

@@ -43,6 +43,18 @@ struct CascadeItem {
     int32_t pad1;
 };
 
+// Where a growing node's next token goes (decode-step advance): one record per copy of
+// the node's tail in Plan::runs.  The token joins run `r_last` if that run ends at the
+// node's end and has room, else the spare run `r_spare` that follows it.  24 bytes, read
+// by the advance kernel.
+struct AdvEntry {
+    int32_t r_last;
+    int32_t r_spare;
+    int64_t end0;       // first free pool row of the node when the plan was built
+    int32_t mergeable;  // 1: run r_last ends at end0
+    int32_t pad;
+};
+
 struct PlanOptions {
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
@@ -70,8 +82,23 @@ struct Plan {
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
     int32_t n_single = 0;             // cascade_items[0, n_single): one workgroup each; the rest:
                                       // small items, four to a workgroup (one wave each)
+    // decode-step advance: every distinct node of leaf_node grows by one token
+    std::vector<AdvEntry> adv;        // tails to extend
+    std::vector<int32_t> adv_node;    // distinct leaf nodes, in order of first appearance
+    std::vector<int32_t> adv_src;     // first leaf query of that node (supplies the new token)
+    std::vector<int64_t> adv_row0;    // first free pool row of that node at plan time
+    bool adv_in_place = false;        // every tail has a record (else advancing re-plans)
+    int32_t adv_room = 0;             // advances the spare runs still hold
+    int32_t advances = 0;             // advances applied in place since the plan was built
+    int32_t piece = 0;                // longest run the kernels accept (0 = any)
     ets_stats stats{};
 };
+
+// Grows every distinct leaf node by one token in place.  Returns false (and changes
+// nothing) when the plan has no room left: the caller then re-plans.
+bool advance_in_place(Plan& plan);
+// The same bookkeeping on the plan's copy of the tree only (lengths and statistics).
+void advance_tree(Plan& plan);
 
 // Builds `plan` from `tree`.  Returns ETS_OK, ETS_ERR_BAD_TREE, ETS_ERR_BAD_LEAF,
 // ETS_ERR_INVALID_ARG or ETS_ERR_NOMEM; on error plan.valid is false.

@@ -511,8 +511,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                     const int sidx = 2 * tile + st;
                     if (sidx >= n_steps) break;
                     const int n_valid = __builtin_amdgcn_readfirstlane(sm_desc[sidx][2]);
-                    attn_step<true>(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
-                                    n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
+                    if (n_valid > 0)  // an empty spare step was never staged
+                        attn_step<true>(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
+                                        n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
                 }
             }
 

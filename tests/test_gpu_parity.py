@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2502_13575_amd as ets
 from workload import (CONFIGS, TreeConfig, make_tree, make_values_device, make_values_host,
                       random_tree)
@@ -205,3 +206,55 @@ def test_long_chain_of_one_token_nodes():
         out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q))
     compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
             oo.reshape(-1, 128), ol.reshape(-1), "bf16", "chain")
+
+
+@pytest.mark.parametrize("name,opts,steps", [("c2_w16", {}, 40), ("c2_w16", {"mfma": 0}, 6),
+                                             ("c1_tiny", {}, 6), ("c3_pruned", {}, 36)])
+def test_decode_loop_append_advance_attend(name, opts, steps):
+    """Decode steps on one plan: append every leaf's new K/V row, advance the plan, attend.
+    Each step's output equals the oracle on the explicitly grown tree; the pools end up
+    bitwise equal to the oracle's."""
+    from workload import with_growth_room, make_new_tokens_host
+    cfg = CONFIGS[name]
+    tree = with_growth_room(make_tree(cfg), steps + 2)
+    k, v, q = make_values_host(cfg, tree)
+    kd, vd, qd = to_device(k), to_device(v), to_device(q)
+    n_tokens = tree.n_tokens.copy()
+    L, hq, d = tree.n_leaves, cfg.n_q_heads, cfg.head_dim
+    replans = 0
+    with make_ctx(cfg, opts) as ctx:
+        st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        for step in range(steps):
+            kn, vn = make_new_tokens_host(cfg, tree, step)
+            n_tokens = oracle.append_kv(tree.tok_offset, n_tokens, tree.leaf_node, k, v, kn, vn)
+            ctx.kv_append(kd, vd, tree.pool_tokens, to_device(kn), to_device(vn))
+            if ctx.plan_advance():
+                replans += 1
+                st = ctx.stats()
+            out = torch.full((L, hq, d), float("nan"), dtype=torch.float32, device="cuda:0")
+            lse = torch.full((L, hq), float("nan"), dtype=torch.float32, device="cuda:0")
+            ws = torch.empty(max(st.workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+            ctx.decode(kd, vd, tree.pool_tokens, qd, out, lse, ws, ws.numel())
+            torch.cuda.synchronize()
+            if step % 5 == 0 or step >= steps - 3:
+                grown = type(tree)(tree.parent, tree.tok_offset, n_tokens, tree.leaf_node,
+                                   tree.pool_tokens)
+                oo, ol = oracle_full(cfg, grown, k, v, q)
+                compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                        oo.reshape(-1, d), ol.reshape(-1), cfg.dtype, "%s step %d" % (name, step))
+    from _gpu_util import to_host_bits
+    assert np.array_equal(to_host_bits(kd), k) and np.array_equal(to_host_bits(vd), v)
+    if steps > 33 and opts.get("mfma", 1):
+        assert replans >= 1
+
+
+def test_kv_append_rejects_a_pool_without_room():
+    from workload import with_growth_room
+    cfg = CONFIGS["c2_w16"]
+    tree = make_tree(cfg)  # packed: no free row behind the last node
+    k, v, q = (to_device(x) for x in make_values_host(cfg, tree))
+    with make_ctx(cfg) as ctx:
+        ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        with pytest.raises(ets.EtsError) as e:
+            ctx.kv_append(k, v, tree.pool_tokens, q, q)
+        assert e.value.status == 1  # ETS_ERR_INVALID_ARG

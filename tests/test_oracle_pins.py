@@ -13,7 +13,7 @@ import torch
 
 import oracle
 from workload import (CONFIGS, bf16_bits_to_f32, make_tree, make_values_host,
-                      random_tree, to_bf16_bits)
+                      random_tree, to_bf16_bits, Tree)
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
 
@@ -364,3 +364,41 @@ def test_generator_is_deterministic_and_variants_share_lengths():
     k1 = make_values_host(CONFIGS["c2_w16"], make_tree(CONFIGS["c2_w16"]))[0]
     k2 = make_values_host(CONFIGS["c2_w16"], make_tree(CONFIGS["c2_w16"]))[0]
     assert np.array_equal(k1, k2)
+
+
+# ------------------------------------------------------- decode-step advance
+def test_append_kv_closed_forms():
+    """After t appended tokens with q = 0 every LSE is ln(n_path + t); a dominant
+    appended key turns the output into exactly that token's V row (GQA-mapped)."""
+    from workload import with_growth_room, make_new_tokens_host
+    cfg = CONFIGS["c1_tiny"]
+    t = with_growth_room(make_tree(cfg), 4)
+    k, v, q = make_values_host(cfg, t)
+    base = [len(_py_rows(t, l)) for l in range(t.n_leaves)]
+    n_tokens = t.n_tokens
+    for step in range(3):
+        kn, vn = make_new_tokens_host(cfg, t, step)
+        n_tokens = oracle.append_kv(t.tok_offset, n_tokens, t.leaf_node, k, v, kn, vn)
+    grown = Tree(t.parent, t.tok_offset, n_tokens, t.leaf_node, t.pool_tokens)
+    out, lse = _run(grown, k, v, np.zeros_like(q), cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim)
+    for l in range(t.n_leaves):
+        assert np.allclose(lse[l], math.log(base[l] + 3), rtol=0, atol=1e-13)
+    # a fourth token whose key is 200 q / |q|^2-aligned dominates every other score
+    kn, vn = make_new_tokens_host(cfg, t, 3)
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    for l in range(t.n_leaves):
+        kn[l, :, :] = 0
+        for h in range(cfg.n_kv_heads):
+            kn[l, h, :] = 60.0 * q[l, h * G, :] / np.dot(q[l, h * G], q[l, h * G]) * math.sqrt(cfg.head_dim)
+    n_tokens = oracle.append_kv(t.tok_offset, n_tokens, t.leaf_node, k, v, kn, vn)
+    grown = Tree(t.parent, t.tok_offset, n_tokens, t.leaf_node, t.pool_tokens)
+    out, lse = _run(grown, k, v, q, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim)
+    for l in range(t.n_leaves):
+        for h in range(cfg.n_kv_heads):
+            assert np.allclose(out[l, h * G], vn[l, h].astype(np.float64), rtol=0, atol=1e-9)
+    # rows written: exactly the first free row of every leaf node, nothing else moved
+    k2, v2, _ = make_values_host(cfg, t)
+    changed = np.nonzero((k2 != k).any(axis=(1, 2)))[0]
+    want = np.sort(np.concatenate([t.tok_offset[n] + t.n_tokens[n] + np.arange(4)
+                                   for n in np.unique(t.leaf_node)]))
+    assert np.array_equal(changed, want)

@@ -200,3 +200,71 @@ def test_long_chain_of_one_token_nodes_is_cut_into_bounded_step_lists():
             rows, _ = ctx.leaf_cover(l)
             want = off[:leaf[l] + 1]
             assert np.array_equal(np.sort(rows), np.sort(want))
+
+
+# ------------------------------------------------------- decode-step advance
+def _check_cover(ctx, t, n_tokens):
+    grown = type(t)(t.parent, t.tok_offset, n_tokens, t.leaf_node, t.pool_tokens)
+    st = ctx.stats()
+    ost = oracle.tree_stats(grown.parent, grown.n_tokens, grown.leaf_node)
+    assert st.unique_tokens == ost["unique_tokens"] and st.flat_tokens == ost["flat_tokens"]
+    assert st.min_pool_tokens == max(int((grown.tok_offset + grown.n_tokens)[
+        ost["leaf_count"] > 0].max(initial=0)), 0)
+    optr, onodes = oracle.paths(grown.parent, grown.leaf_node)
+    total = 0
+    for l in range(grown.n_leaves):
+        rows, npart = ctx.leaf_cover(l)
+        assert np.array_equal(np.sort(rows), np.sort(_chain_rows(grown, optr, onodes, l))), l
+        total += npart
+    assert total == st.n_partials
+
+
+@pytest.mark.parametrize("name,opts", [("c2_w16", {}), ("c2_w16", {"mfma": 0}),
+                                       ("c1_tiny", {}), ("c3_pruned", {"cascade_min_leaves": 0})])
+def test_plan_advance_tracks_oracle_walk(name, opts):
+    """Every advance makes every distinct leaf node one token longer: rows read per leaf
+    and the statistics equal the oracle's walk of the grown tree, through in-place
+    advances and through the re-plan that follows when the step lists are full."""
+    from workload import with_growth_room
+    cfg = CONFIGS[name]
+    t = with_growth_room(make_tree(cfg), 80)
+    with _ctx(cfg) as ctx:
+        for k, v in opts.items():
+            ctx.set_option(k, v)
+        ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        n_tokens = t.n_tokens.copy()
+        replans = 0
+        for step in range(75):
+            replans += int(ctx.plan_advance())
+            n_tokens[np.unique(t.leaf_node)] += 1
+            if step % 6 == 0 or step > 70:
+                _check_cover(ctx, t, n_tokens)
+        limited = cfg.dtype == "bf16" and cfg.head_dim == 128 and opts.get("mfma", 1) != 0
+        assert (replans >= 1) if limited else (replans == 0)
+        assert replans <= 3
+
+
+def test_plan_advance_fuzz_and_duplicates():
+    from workload import with_growth_room
+    for seed in range(6):
+        t = with_growth_room(random_tree(100 + seed, 40, 12, 70), 40)
+        with _ctx((2, 8, 128, ets.ETS_BF16)) as ctx:
+            ctx.set_option("stream_chunk", [0, 32, 64][seed % 3])
+            ctx.set_option("wave_items", [512, 0][seed % 2])
+            ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            n_tokens = t.n_tokens.copy()
+            for step in range(36):
+                ctx.plan_advance()
+                n_tokens[np.unique(t.leaf_node)] += 1
+                if step % 5 == 0 or step >= 33:
+                    _check_cover(ctx, t, n_tokens)
+
+
+def test_advance_and_append_error_paths():
+    with _ctx((2, 8, 128, ets.ETS_BF16)) as ctx:
+        with pytest.raises(ets.EtsError) as e:
+            ctx.plan_advance()
+        assert e.value.status == 6  # ETS_ERR_NO_PLAN
+        with pytest.raises(ets.EtsError) as e:
+            ctx.kv_append(None, None, 0, None, None)
+        assert e.value.status == 6

@@ -211,3 +211,31 @@ def make_values_device(cfg: TreeConfig, tree: Tree, device, seed: Optional[int] 
         v[l].normal_(generator=g)
         q[l].normal_(generator=g)
     return k, v, q
+
+
+def with_growth_room(tree: Tree, room: int) -> Tree:
+    """The same tree laid out with `room` free pool rows after every node that holds a
+    leaf query (as a cache reserves space for the step being generated), so that decode
+    steps can append tokens to those nodes.  Nodes keep their order in the pool."""
+    is_leaf = np.zeros(tree.n_nodes, dtype=bool)
+    is_leaf[tree.leaf_node] = True
+    order = np.argsort(tree.tok_offset, kind="stable")
+    new_off = np.zeros(tree.n_nodes, dtype=np.int64)
+    cur = 0
+    for n in order:
+        new_off[n] = cur
+        cur += int(tree.n_tokens[n]) + (room if is_leaf[n] else 0)
+    return Tree(tree.parent.copy(), new_off, tree.n_tokens.copy(), tree.leaf_node.copy(),
+                max(cur, 1), tree.step)
+
+
+def make_new_tokens_host(cfg: TreeConfig, tree: Tree, step: int, seed: Optional[int] = None):
+    """K and V rows of the token every leaf query generates at decode step `step`:
+    [L, Hkv, D] each, i.i.d. N(0,1), in the pool's dtype convention."""
+    seed = cfg.seed if seed is None else seed
+    r = _rng(seed, 1000 + step)
+    k = r.standard_normal((tree.n_leaves, cfg.n_kv_heads, cfg.head_dim), dtype=np.float32)
+    v = r.standard_normal((tree.n_leaves, cfg.n_kv_heads, cfg.head_dim), dtype=np.float32)
+    if cfg.dtype == "bf16":
+        return to_bf16_bits(k), to_bf16_bits(v)
+    return k, v
