@@ -74,6 +74,8 @@ def main():
                     help="CPU time budget of the oracle baseline sample (0 = skip)")
     ap.add_argument("--flat-steps", type=int, default=2, help="timed steps of the flat baseline (0 = skip)")
     ap.add_argument("--option", action="append", default=[], help="planner knob key=value")
+    ap.add_argument("--decode-tokens", type=int, default=8,
+                    help="decode tokens of the append/advance measurement on one extra pool (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "scaling hardware byte counters when profiling)")
@@ -213,6 +215,54 @@ def main():
                 "flat_over_unique_bytes": round(st.flat_kv_bytes / max(st.unique_kv_bytes, 1), 2)}
         log("flat baseline: %.3f ms/step -> tree is %.2fx faster" % (flat_ms, flat_ms / ms_per_step))
 
+    decode_step = None
+    if args.decode_tokens > 0:
+        # Decode-step advance on one extra pool with room behind every leaf node: per token,
+        # append every leaf's K/V row, advance the plan, attend (one layer).
+        from workload import with_growth_room
+        n_tok = args.decode_tokens
+        roomy = with_growth_room(tree, n_tok + 1)
+        t0 = time.perf_counter()
+        st_r = ctx.plan(roomy.parent, roomy.tok_offset, roomy.n_tokens, roomy.leaf_node,
+                        ets.ETS_PLAN_TREE)
+        plan_r_ms = (time.perf_counter() - t0) * 1e3
+        kshape = (roomy.pool_tokens, cfg.n_kv_heads, d)
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        kr = torch.randn(kshape, device=dev, dtype=torch.float32).to(tdt)
+        vr = torch.randn(kshape, device=dev, dtype=torch.float32).to(tdt)
+        knew = torch.randn((L, cfg.n_kv_heads, d), device=dev, dtype=torch.float32).to(tdt)
+        vnew = torch.randn((L, cfg.n_kv_heads, d), device=dev, dtype=torch.float32).to(tdt)
+        ws = torch.empty(max(st_r.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_tok)]
+        adv_host = 0.0
+        replans = 0
+        torch.cuda.synchronize()
+        for i in range(n_tok):
+            ev[2 * i].record()
+            ctx.kv_append(kr, vr, roomy.pool_tokens, knew, vnew, stream.cuda_stream)
+            ev[2 * i + 1].record()
+            t0 = time.perf_counter()
+            if ctx.plan_advance(stream.cuda_stream):
+                replans += 1
+                st_r = ctx.stats()
+                ws = torch.empty(max(st_r.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+            adv_host += time.perf_counter() - t0
+            ctx.decode(kr, vr, roomy.pool_tokens, qd[0], out[0], lse[0], ws, ws.numel(),
+                       stream.cuda_stream)
+        torch.cuda.synchronize()
+        app_us = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(n_tok)) / n_tok * 1e3
+        n_nodes = len(np.unique(roomy.leaf_node))
+        app_bytes = 4 * n_nodes * cfg.n_kv_heads * d * cfg.elem_bytes   # K and V, read + written
+        decode_step = {"tokens": n_tok, "plan_ms": round(plan_r_ms, 3),
+                       "advance_host_us": round(adv_host / n_tok * 1e6, 1), "replans": replans,
+                       "append_us_per_layer": round(app_us, 2),
+                       "append_bytes_per_layer": app_bytes,
+                       "append_GBps": round(app_bytes / (app_us * 1e-6) / 1e9, 1)}
+        log("decode step: plan %.2f ms, advance %.1f us (host), append %.2f us per layer "
+            "(%d nodes, %.1f GB/s; launch-bound)" % (plan_r_ms, adv_host / n_tok * 1e6, app_us,
+                                                      n_nodes, decode_step["append_GBps"]))
+        del kr, vr, ws
+
     cpu = None
     parity = None
     if args.cpu_seconds > 0:
@@ -285,6 +335,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "flat_baseline": flat,
+        "decode_step": decode_step,
         "parity_sample": parity,
         "paper_context": "ETS reports 1.8x smaller KV and 1.4x search throughput vs REBASE on "
                          "2x H100 NVL with stock kernels; no kernel-level numbers",
