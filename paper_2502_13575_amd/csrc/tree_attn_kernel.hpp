@@ -6,17 +6,20 @@
 // queries that attend to them.  The workgroup reads the item's K and V from
 // HBM exactly once, 64 tokens (two steps) at a time, stages them in LDS and
 // applies them to all R = n_ent * G <= 64 query rows (the G query heads of a
-// leaf share the kv head).  Each wave fetches and stages half a step (16
-// tokens) and owns at most one block of 16 query rows, which keeps the kernel
-// at 168 registers per lane and 38 KB of LDS: three workgroups (12 waves) per
+// leaf share the kv head).  Each wave fetches half a step (16 tokens) and owns
+// at most one block of 16 query rows, which keeps the kernel under 170
+// registers per lane and at 38 KB of LDS: three workgroups (12 waves) per
 // compute unit, so that one workgroup's memory latency overlaps the others'
 // arithmetic.
-//   R  > 16  "row parallel":   wave w owns row block w and walks both steps of
-//            every tile; the staged tile is reused by the waves.
-//   R <= 16  "token parallel": waves 0 and 2 each walk one of the tile's two
-//            steps for the single row block; their two running results are
-//            folded through LDS at the end, so the item still yields one
+//   R  > 16  "row parallel":   the tile is staged in LDS once and reused by the
+//            waves; wave w owns row block w and walks both steps of every tile.
+//   R <= 16  "token parallel": nothing is shared, so every wave walks the
+//            16-token units it fetched itself through a private LDS region,
+//            with no workgroup barrier in the loop; the four running results
+//            are folded through LDS at the end, so the item still yields one
 //            partial per query row.
+//   small items (R <= 16, few tokens): four items per workgroup, each walked by
+//            one wave alone, without fold or barrier.
 //
 // bf16 pools, head_dim 128.  Per step of 32 tokens and block of 16 query rows:
 //   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, tokens on M, query rows on N:
@@ -62,18 +65,12 @@ __device__ __forceinline__ f16x8_t as_f16x8(u32x4_t v) { return __builtin_bit_ca
 __device__ __forceinline__ u32x4_t load16(const void* p) {
     return *reinterpret_cast<const u32x4_t*>(p);
 }
-// Two bf16 packed in a dword -> the same two values as packed fp16.
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(v), bf16_hi(v)));
-}
-
 constexpr int kTreeAttnRowsPerItem = 64;  // 4 waves x 16 rows
 constexpr int kTreeAttnMaxSteps = 256;    // steps per work item (planner's cap)
 constexpr int kTreeAttnKRow = 17;         // 16-byte units per padded K row in LDS (272 bytes)
 
-// One step: 32 staged tokens against one block of 16 query rows.  F16V tells
-// how V was staged (fp16, or bf16 with split weights).
-template <bool F16V>
+// One step of a row-parallel item: 32 staged tokens (V already fp16) against one block
+// of 16 query rows.
 __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
                                           const u32x4_t* __restrict__ vs_lane, int b, int n_valid,
                                           const bf16x8_t (&qf)[4], f32x4_t (&oacc)[8], float& m,
@@ -109,35 +106,17 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
     }
     const float mc = m * scale_log2e;
     float psum = 0.f;
-    if constexpr (F16V) {
-        f16x8_t pf;
+    f16x8_t pf;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(fmaf(s[j], scale_log2e, -mc));
-            psum += p;
-            pf[j] = (_Float16)p;
-        }
-#pragma unroll
-        for (int x = 0; x < 8; ++x)
-            oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vs_lane[x * 64]), pf, oacc[x],
-                                                             0, 0, 0);
-    } else {
-        bf16x8_t ph, pl;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(fmaf(s[j], scale_log2e, -mc));
-            psum += p;
-            const __bf16 hi = (__bf16)p;
-            ph[j] = hi;
-            pl[j] = (__bf16)(p - (float)hi);
-        }
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            const bf16x8_t vf = as_bf16x8(vs_lane[x * 64]);
-            oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, ph, oacc[x], 0, 0, 0);
-            oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, oacc[x], 0, 0, 0);
-        }
+    for (int j = 0; j < 8; ++j) {
+        const float p = fast_exp2(fmaf(s[j], scale_log2e, -mc));
+        psum += p;
+        pf[j] = (_Float16)p;
     }
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+        oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vs_lane[x * 64]), pf, oacc[x], 0,
+                                                         0, 0);
     lsum += psum;
 }
 
@@ -512,7 +491,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                     if (sidx >= n_steps) break;
                     const int n_valid = __builtin_amdgcn_readfirstlane(sm_desc[sidx][2]);
                     if (n_valid > 0)  // an empty spare step was never staged
-                        attn_step<true>(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
+                        attn_step(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
                                         n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
                 }
             }
