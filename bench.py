@@ -226,7 +226,7 @@ def main():
         st_r = ctx.plan(roomy.parent, roomy.tok_offset, roomy.n_tokens, roomy.leaf_node,
                         ets.ETS_PLAN_TREE)
         plan_r_ms = (time.perf_counter() - t0) * 1e3
-        kshape = (roomy.pool_tokens, cfg.n_kv_heads, d)
+        kshape = (cfg.n_kv_heads, roomy.pool_tokens, d)
         tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
         kr = torch.randn(kshape, device=dev, dtype=torch.float32).to(tdt)
         vr = torch.randn(kshape, device=dev, dtype=torch.float32).to(tdt)
@@ -271,6 +271,8 @@ def main():
             if cfg.dtype == "bf16" else kd[0].cpu().numpy()
         vh = vd[0].contiguous().view(torch.int16).cpu().numpy().view(np.uint16) \
             if cfg.dtype == "bf16" else vd[0].cpu().numpy()
+        # device pools are [kv head][pool row][D]; the oracle indexes [row, head, :]
+        kh, vh = kh.transpose(1, 0, 2), vh.transpose(1, 0, 2)
         qh = qd[0].contiguous().view(torch.int16).cpu().numpy().view(np.uint16) \
             if cfg.dtype == "bf16" else qd[0].cpu().numpy()
         r = np.random.default_rng(2024)

@@ -18,7 +18,9 @@
  *     lse[l,j] = ln sum_t exp(s_t)                 (natural log)
  *     out[l,j] = sum_t exp(s_t - lse[l,j]) * V[t,h,:]
  *
- * with no mask (the query is the newest position of its trajectory).  A leaf
+ * (K[t,h,:] = row t of kv head h; in memory the pools are head-major, see
+ * ets_tree_decode_attn) with no mask (the query is the newest position of its
+ * trajectory).  A leaf
  * whose chain holds no tokens gets out = 0 and lse = -inf.
  *
  * Conventions
@@ -162,8 +164,8 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
  * at pool row tok_offset[node] + n_tokens[node] (the plan's current lengths), which
  * the caller must have reserved for that node.
  *   k_pool, v_pool  DEVICE, as in ets_tree_decode_attn, written
- *   pool_tokens     rows in each pool; must exceed every written row, else
- *                   ETS_ERR_INVALID_ARG and nothing is written
+ *   pool_tokens     rows per head plane, as in ets_tree_decode_attn; must exceed
+ *                   every written row, else ETS_ERR_INVALID_ARG and nothing is written
  *   k_new, v_new    DEVICE, [n_leaves][n_kv_heads][head_dim] of shape.dtype, 16-byte
  *                   aligned: row l is the new token of leaf query l; when several leaf
  *                   queries sit on one node, the first of them supplies the row
@@ -201,8 +203,12 @@ ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned);
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 
 /* One layer of decode attention for every leaf query of the planned tree.
- *   k_pool, v_pool  DEVICE, [pool_tokens][n_kv_heads][head_dim] of shape.dtype,
- *                   16-byte aligned; pool_tokens >= stats.min_pool_tokens
+ *   k_pool, v_pool  DEVICE, [n_kv_heads][pool_tokens][head_dim] of shape.dtype,
+ *                   16-byte aligned: one plane of pool_tokens rows per kv head, so
+ *                   that the rows of a node are contiguous within a head (pool row
+ *                   t of head h starts at element (h * pool_tokens + t) * head_dim)
+ *   pool_tokens     rows per head plane of BOTH pools, i.e. the plane stride (not
+ *                   merely a bound); >= stats.min_pool_tokens, else ETS_ERR_BAD_TREE
  *   q               DEVICE, [n_leaves][n_q_heads][head_dim] of shape.dtype, 16-byte aligned
  *   out             DEVICE, [n_leaves][n_q_heads][head_dim] float
  *   lse             DEVICE, [n_leaves][n_q_heads] float

@@ -52,15 +52,17 @@ def _load():
         lib.ets_oracle_tree_stats.argtypes = [C.c_int32, i32p, i32p, C.c_int32, i32p, i64p,
                                               i64p, i64p, i64p]
         common = [C.c_int32, i32p, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32,
-                  C.c_int32, C.c_int, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+                  C.c_int32, C.c_int, C.c_double, C.c_void_p, C.c_void_p, C.c_int64,
+                  C.c_int64, C.c_void_p]
         lib.ets_oracle_attn.restype = C.c_int
         lib.ets_oracle_attn.argtypes = common + [f64p, f64p]
         lib.ets_oracle_attn_rows.restype = C.c_int
         lib.ets_oracle_attn_rows.argtypes = common + [C.c_int64, i32p, i32p, f64p, f64p]
         lib.ets_oracle_partial.restype = None
-        lib.ets_oracle_partial.argtypes = [C.c_int32, C.c_int32, C.c_int, C.c_double,
-                                           C.c_void_p, C.c_void_p, f64p, C.c_int32,
-                                           C.c_int64, i64p, f64p, f64p, f64p]
+        lib.ets_oracle_partial.argtypes = [C.c_int32, C.c_int, C.c_double,
+                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                           f64p, C.c_int32, C.c_int64, i64p, f64p, f64p,
+                                           f64p]
         lib.ets_oracle_merge.restype = None
         lib.ets_oracle_merge.argtypes = [C.c_int32, C.c_int64, f64p, f64p, f64p, f64p, f64p]
         _lib = lib
@@ -86,6 +88,27 @@ def _vals(a):
     if a.dtype == np.uint16:
         return a, BF16
     raise TypeError("values must be float32 or uint16 (bfloat16 bits), got %s" % a.dtype)
+
+
+def _pool(a):
+    """A pool K[t, h, :] as (array, dtype code, row stride, head stride), strides in
+    elements.  Any memory order of the first two axes is taken as it is (no copy), so a
+    head-major buffer can be handed over as the transposed view buf.transpose(1, 0, 2);
+    only the last axis has to be contiguous."""
+    a = np.asarray(a)
+    if a.ndim != 3:
+        raise ValueError("a pool has three axes: [pool row, kv head, head_dim]")
+    if a.dtype == np.float32:
+        dt = F32
+    elif a.dtype == np.uint16:
+        dt = BF16
+    else:
+        raise TypeError("values must be float32 or uint16 (bfloat16 bits), got %s" % a.dtype)
+    sz = a.dtype.itemsize
+    if a.shape[2] > 1 and a.strides[2] != sz or a.strides[0] % sz or a.strides[1] % sz \
+            or a.strides[0] < 0 or a.strides[1] < 0:
+        a = np.ascontiguousarray(a)
+    return a, dt, a.strides[0] // sz, a.strides[1] // sz
 
 
 def threads() -> int:
@@ -140,13 +163,19 @@ def _tree_args(parent, tok_offset, n_tokens, leaf_node):
 
 def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
                      n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
-    """Oracle attention.  k_pool/v_pool: [pool_tokens, Hkv, D]; q: [L, Hq, D].
+    """Oracle attention.  k_pool/v_pool: K[t, h, :] as arrays of shape [pool_tokens, Hkv, D]
+    (their strides say how the pool lies in memory); q: [L, Hq, D].
 
     rows=None: every (leaf, head) -> out float64 [L, Hq, D], lse float64 [L, Hq].
     rows=(leaf_idx, head_idx): only those pairs -> out [n, D], lse [n].
     """
-    k_pool, dt = _vals(k_pool)
-    v_pool, dt2 = _vals(v_pool)
+    k_pool, dt, ts, hs = _pool(k_pool)
+    v_pool, dt2, ts2, hs2 = _pool(v_pool)
+    if k_pool.shape != v_pool.shape or (ts2, hs2) != (ts, hs):
+        v_pool = np.ascontiguousarray(v_pool)
+        k_pool = np.ascontiguousarray(k_pool)
+        k_pool, dt, ts, hs = _pool(k_pool)
+        v_pool, dt2, ts2, hs2 = _pool(v_pool)
     q, dt3 = _vals(q)
     if not (dt == dt2 == dt3):
         raise TypeError("k, v, q must share one dtype")
@@ -160,7 +189,7 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
     assert q.shape == (L, n_q_heads, head_dim)
     common = targs + [n_kv_heads, n_q_heads, head_dim, dt, float(sm_scale),
                       k_pool.ctypes.data_as(C.c_void_p), v_pool.ctypes.data_as(C.c_void_p),
-                      q.ctypes.data_as(C.c_void_p)]
+                      ts, hs, q.ctypes.data_as(C.c_void_p)]
     if rows is None:
         out = np.zeros((L, n_q_heads, head_dim), dtype=np.float64)
         lse = np.zeros((L, n_q_heads), dtype=np.float64)
@@ -179,15 +208,16 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
 
 def partial(k_pool, v_pool, qvec, kv_head, rows, sm_scale=0.0):
     """Unnormalised partial (o[D], m, l) of one query vector over pool rows `rows`."""
-    k_pool, dt = _vals(k_pool)
-    v_pool, _ = _vals(v_pool)
+    k_pool, dt, ts, hs = _pool(np.ascontiguousarray(k_pool))
+    v_pool, _, _, _ = _pool(np.ascontiguousarray(v_pool))
+    assert k_pool.shape == v_pool.shape
     qvec = np.ascontiguousarray(qvec, dtype=np.float64)
     rows = _i64(rows)
     _, hkv, d = k_pool.shape
     o = np.zeros(d, dtype=np.float64)
     m, l = C.c_double(0), C.c_double(0)
-    _load().ets_oracle_partial(hkv, d, dt, float(sm_scale), k_pool.ctypes.data_as(C.c_void_p),
-                               v_pool.ctypes.data_as(C.c_void_p), _p(qvec, C.c_double),
+    _load().ets_oracle_partial(d, dt, float(sm_scale), k_pool.ctypes.data_as(C.c_void_p),
+                               v_pool.ctypes.data_as(C.c_void_p), ts, hs, _p(qvec, C.c_double),
                                int(kv_head), rows.shape[0], _p(rows, C.c_int64),
                                _p(o, C.c_double), C.byref(m), C.byref(l))
     return o, m.value, l.value

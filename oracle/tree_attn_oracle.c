@@ -18,7 +18,10 @@
  *   LSE[l,j] = m + ln sum_t exp(s_t - m),  m = max_t s_t      (natural log)
  *   O[l,j,:] = sum_t exp(s_t - LSE) * V[t,h,:]
  *
- * all in fp64 after exact widening of the fp32 / bfloat16 inputs.  An empty
+ * all in fp64 after exact widening of the fp32 / bfloat16 inputs.  K[t,h,:] and
+ * V[t,h,:] are D consecutive elements starting at element t * tok_stride +
+ * h * head_stride of their pool, so that any memory order of (row, head) can be
+ * described.  An empty
  * path gives O = 0 and LSE = -inf.  The paper treats the model as a black box,
  * so the attention formula is the standard scaled-dot-product one; the paper
  * supplies the tree and sharing semantics.
@@ -121,8 +124,9 @@ void ets_oracle_tree_stats(int32_t n_nodes, const int32_t* parent, const int32_t
 /* Attention of one (leaf, query head) over its whole path.  out has D entries. */
 static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int32_t* n_tokens,
                     int32_t v, int32_t Hkv, int32_t Hq, int32_t D, int dtype, double scale,
-                    const void* k_pool, const void* v_pool, const void* q, int32_t leaf,
-                    int32_t j, double* out, double* lse) {
+                    const void* k_pool, const void* v_pool, int64_t tok_stride,
+                    int64_t head_stride, const void* q, int32_t leaf, int32_t j, double* out,
+                    double* lse) {
     const int32_t G = Hq / Hkv;
     const int32_t h = j / G;
     const int64_t depth = chain_len(parent, v);
@@ -152,7 +156,7 @@ static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int3
     const int64_t qbase = ((int64_t)leaf * Hq + j) * D;
     double m = -INFINITY;
     for (t = 0; t < n_p; ++t) {
-        const int64_t kbase = (rows[t] * Hkv + h) * D;
+        const int64_t kbase = rows[t] * tok_stride + h * head_stride;
         double acc = 0.0;
         for (int32_t d = 0; d < D; ++d)
             acc += load_elem(q, dtype, qbase + d) * load_elem(k_pool, dtype, kbase + d);
@@ -164,7 +168,7 @@ static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int3
     *lse = m + log(sum);
     for (t = 0; t < n_p; ++t) {
         const double w = exp(s[t] - *lse);
-        const int64_t vbase = (rows[t] * Hkv + h) * D;
+        const int64_t vbase = rows[t] * tok_stride + h * head_stride;
         for (int32_t d = 0; d < D; ++d) out[d] += w * load_elem(v_pool, dtype, vbase + d);
     }
     free(path); free(rows); free(s);
@@ -176,7 +180,8 @@ static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int3
 int ets_oracle_attn_rows(int32_t n_nodes, const int32_t* parent, const int64_t* tok_offset,
                          const int32_t* n_tokens, int32_t n_leaves, const int32_t* leaf_node,
                          int32_t Hkv, int32_t Hq, int32_t D, int dtype, double scale,
-                         const void* k_pool, const void* v_pool, const void* q, int64_t n_sel,
+                         const void* k_pool, const void* v_pool, int64_t tok_stride,
+                         int64_t head_stride, const void* q, int64_t n_sel,
                          const int32_t* sel_leaf, const int32_t* sel_head, double* out,
                          double* lse) {
     (void)n_nodes;
@@ -192,7 +197,7 @@ int ets_oracle_attn_rows(int32_t n_nodes, const int32_t* parent, const int64_t* 
             continue;
         }
         int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], Hkv, Hq, D, dtype, scale,
-                         k_pool, v_pool, q, l, j, out + i * D, lse + i);
+                         k_pool, v_pool, tok_stride, head_stride, q, l, j, out + i * D, lse + i);
         if (e) {
 #pragma omp atomic write
             err = e;
@@ -205,8 +210,8 @@ int ets_oracle_attn_rows(int32_t n_nodes, const int32_t* parent, const int64_t* 
 int ets_oracle_attn(int32_t n_nodes, const int32_t* parent, const int64_t* tok_offset,
                     const int32_t* n_tokens, int32_t n_leaves, const int32_t* leaf_node,
                     int32_t Hkv, int32_t Hq, int32_t D, int dtype, double scale,
-                    const void* k_pool, const void* v_pool, const void* q, double* out,
-                    double* lse) {
+                    const void* k_pool, const void* v_pool, int64_t tok_stride,
+                    int64_t head_stride, const void* q, double* out, double* lse) {
     (void)n_nodes;
     if (Hkv <= 0 || Hq % Hkv != 0 || D <= 0) return 2;
     if (scale <= 0.0) scale = 1.0 / sqrt((double)D);
@@ -216,7 +221,7 @@ int ets_oracle_attn(int32_t n_nodes, const int32_t* parent, const int64_t* tok_o
     for (int64_t i = 0; i < n; ++i) {
         const int32_t l = (int32_t)(i / Hq), j = (int32_t)(i % Hq);
         int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], Hkv, Hq, D, dtype, scale,
-                         k_pool, v_pool, q, l, j, out + i * D, lse + i);
+                         k_pool, v_pool, tok_stride, head_stride, q, l, j, out + i * D, lse + i);
         if (e) {
 #pragma omp atomic write
             err = e;
@@ -228,8 +233,9 @@ int ets_oracle_attn(int32_t n_nodes, const int32_t* parent, const int64_t* tok_o
 /* Partial result of one query vector over an explicit list of pool rows:
  *   m = max_t s_t,  l = sum_t exp(s_t - m),  o[d] = sum_t exp(s_t - m) V[t,h,d]
  * (unnormalised).  n_rows == 0 gives m = -inf, l = 0, o = 0. */
-void ets_oracle_partial(int32_t Hkv, int32_t D, int dtype, double scale, const void* k_pool,
-                        const void* v_pool, const double* qvec, int32_t h, int64_t n_rows,
+void ets_oracle_partial(int32_t D, int dtype, double scale, const void* k_pool,
+                        const void* v_pool, int64_t tok_stride, int64_t head_stride,
+                        const double* qvec, int32_t h, int64_t n_rows,
                         const int64_t* rows, double* o, double* m_out, double* l_out) {
     if (scale <= 0.0) scale = 1.0 / sqrt((double)D);
     for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
@@ -239,7 +245,7 @@ void ets_oracle_partial(int32_t Hkv, int32_t D, int dtype, double scale, const v
     double* s = (double*)malloc(sizeof(double) * (size_t)n_rows);
     double m = -INFINITY;
     for (int64_t t = 0; t < n_rows; ++t) {
-        const int64_t kbase = (rows[t] * Hkv + h) * D;
+        const int64_t kbase = rows[t] * tok_stride + h * head_stride;
         double acc = 0.0;
         for (int32_t d = 0; d < D; ++d) acc += qvec[d] * load_elem(k_pool, dtype, kbase + d);
         s[t] = scale * acc;
@@ -249,7 +255,7 @@ void ets_oracle_partial(int32_t Hkv, int32_t D, int dtype, double scale, const v
     for (int64_t t = 0; t < n_rows; ++t) {
         const double p = exp(s[t] - m);
         l += p;
-        const int64_t vbase = (rows[t] * Hkv + h) * D;
+        const int64_t vbase = rows[t] * tok_stride + h * head_stride;
         for (int32_t d = 0; d < D; ++d) o[d] += p * load_elem(v_pool, dtype, vbase + d);
     }
     free(s);

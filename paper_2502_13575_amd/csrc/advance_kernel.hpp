@@ -27,25 +27,31 @@ __global__ void advance_runs_kernel(Run* __restrict__ runs, const AdvEntry* __re
     }
 }
 
-// One workgroup per growing node: row_bytes = n_kv_heads * head_dim * element size
-// (a multiple of 16) of K and of V go from row src[node] of k_new / v_new to pool row
-// row0[node] + advances.
+// One workgroup per growing node: for every kv head, head_bytes = head_dim * element
+// size (a multiple of 16) of K and of V go from row src[node] of k_new / v_new
+// ([leaf][kv head][head_dim]) to row row0[node] + advances of that head's plane of the
+// pool ([kv head][pool row][head_dim]).
 __global__ __launch_bounds__(256) void kv_append_kernel(char* __restrict__ k_pool,
                                                         char* __restrict__ v_pool,
                                                         const char* __restrict__ k_new,
                                                         const char* __restrict__ v_new,
                                                         const int32_t* __restrict__ src,
                                                         const int64_t* __restrict__ row0,
-                                                        int advances, int row_bytes) {
+                                                        int advances, int n_kv_heads,
+                                                        int head_bytes, int64_t pool_tokens) {
     const int node = blockIdx.x;
-    const int64_t dst = (row0[node] + advances) * (int64_t)row_bytes;
-    const int64_t from = (int64_t)src[node] * row_bytes;
-    const int pieces = row_bytes / 16;
+    const int64_t row = row0[node] + advances;
+    const int64_t from = (int64_t)src[node] * n_kv_heads * head_bytes;
+    const int per_head = head_bytes / 16;
+    const int pieces = n_kv_heads * per_head;
     for (int i = threadIdx.x; i < 2 * pieces; i += blockDim.x) {
         const bool is_v = i >= pieces;
-        const int off = (is_v ? i - pieces : i) * 16;
-        const uint4 val = *reinterpret_cast<const uint4*>((is_v ? v_new : k_new) + from + off);
-        *reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + dst + off) = val;
+        const int piece = is_v ? i - pieces : i;
+        const int h = piece / per_head;
+        const int64_t dst = (h * pool_tokens + row) * head_bytes + (piece - h * per_head) * 16;
+        const uint4 val =
+            *reinterpret_cast<const uint4*>((is_v ? v_new : k_new) + from + piece * 16);
+        *reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + dst) = val;
     }
 }
 

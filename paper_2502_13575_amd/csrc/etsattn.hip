@@ -140,6 +140,7 @@ ets_status upload_plan(ets_ctx* c) {
 
 struct LaunchArgs {
     const void *k, *v, *q;
+    int64_t pool_tokens;
     float* out;
     float* lse;
     float* ws_o;
@@ -154,7 +155,7 @@ void launch_stream(const ets_ctx* c, const LaunchArgs& a) {
     if (n_items == 0) return;
     const unsigned grid = (unsigned)(n_items * c->shape.n_kv_heads);
     hipLaunchKernelGGL((stream_attn_kernel<T, D, G, U>), dim3(grid), dim3(64), 0, a.stream,
-                       static_cast<const T*>(a.k), static_cast<const T*>(a.v),
+                       static_cast<const T*>(a.k), static_cast<const T*>(a.v), a.pool_tokens,
                        static_cast<const T*>(a.q), c->d_runs, c->d_stream, c->shape.n_kv_heads,
                        c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
 }
@@ -182,8 +183,8 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
         hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0,
                            a.stream, static_cast<const bf16_t*>(a.k),
-                           static_cast<const bf16_t*>(a.v), static_cast<const bf16_t*>(a.q),
-                           c->d_runs, c->d_cascade, (int)y0, (int)n_single, (int)n_items,
+                           static_cast<const bf16_t*>(a.v), a.pool_tokens,
+                           static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0, (int)n_single, (int)n_items,
                            c->d_ent_order, c->d_ent_base, g_shift,
                            c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
     }
@@ -361,14 +362,15 @@ ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_
     // every node's next row has to exist in the pool
     if (pool_tokens < p.stats.min_pool_tokens + 1) return ETS_ERR_INVALID_ARG;
     const int64_t esz = ctx->shape.dtype == ETS_F32 ? 4 : 2;
-    const int row_bytes = (int)(ctx->shape.n_kv_heads * (int64_t)ctx->shape.head_dim * esz);
+    const int head_bytes = (int)(ctx->shape.head_dim * esz);
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return ETS_ERR_HIP;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)n), dim3(256), 0, stream,
                        static_cast<char*>(k_pool), static_cast<char*>(v_pool),
                        static_cast<const char*>(k_new), static_cast<const char*>(v_new),
-                       ctx->d_adv_src, ctx->d_adv_row0, (int)p.advances, row_bytes);
+                       ctx->d_adv_src, ctx->d_adv_row0, (int)p.advances, ctx->shape.n_kv_heads,
+                       head_bytes, pool_tokens);
     if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
     ctx->last_stream = stream;
     ctx->stream_used = true;
@@ -457,6 +459,7 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
     a.k = k_pool;
     a.v = v_pool;
     a.q = q;
+    a.pool_tokens = pool_tokens;
     a.out = out;
     a.lse = lse;
     a.ws_o = static_cast<float*>(workspace);

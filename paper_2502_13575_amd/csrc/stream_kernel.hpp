@@ -19,8 +19,9 @@ namespace ets {
 
 template <typename T, int D, int G, int U>
 __global__ __launch_bounds__(64) void stream_attn_kernel(
-    const T* __restrict__ k_pool, const T* __restrict__ v_pool, const T* __restrict__ q,
-    const Run* __restrict__ runs, const StreamItem* __restrict__ items, int n_kv_heads,
+    const T* __restrict__ k_pool, const T* __restrict__ v_pool, int64_t pool_tokens,
+    const T* __restrict__ q, const Run* __restrict__ runs, const StreamItem* __restrict__ items,
+    int n_kv_heads,
     float scale_log2e, float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
     constexpr int EPL = Vec16<T>::N;  // elements per lane per load
     constexpr int LPT = D / EPL;      // lanes per token row
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(64) void stream_attn_kernel(
     const int a = lane % LPT;  // which 16-byte piece of the row
     const int b = lane / LPT;  // which token of the step
     const int n_q_heads = n_kv_heads * G;
-    const int64_t row_stride = (int64_t)n_kv_heads * D;
+    constexpr int64_t row_stride = D;  // pools are [kv head][pool row][D]
 
     float qf[G][EPL];
     {
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(64) void stream_attn_kernel(
 
     for (int r = item.run_begin; r < item.run_end; ++r) {
         const Run run = runs[r];
-        const int64_t base = (run.tok * n_kv_heads + h) * (int64_t)D + a * EPL;
+        const int64_t base = ((int64_t)h * pool_tokens + run.tok) * (int64_t)D + a * EPL;
         const T* kb = k_pool + base;
         const T* vb = v_pool + base;
         for (int t0 = 0; t0 < run.n; t0 += TPS * U) {

@@ -21,7 +21,8 @@
 //   small items (R <= 16, few tokens): four items per workgroup, each walked by
 //            one wave alone, without fold or barrier.
 //
-// bf16 pools, head_dim 128.  Per step of 32 tokens and block of 16 query rows:
+// bf16 pools laid out [kv head][pool row][128]: the rows of a step are contiguous
+// within a head, 256 bytes each.  Per step of 32 tokens and block of 16 query rows:
 //   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, tokens on M, query rows on N:
 //                  A = K rows (8 consecutive d per lane, read from the LDS tile),
 //                  B = Q rows (registers).
@@ -171,7 +172,7 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
-    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
+    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
     const CascadeItem* __restrict__ items, int wg_base, int n_single, int n_items,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
@@ -222,7 +223,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
 
     // wave w fetches half hw of step 2 tile + sw of every tile
     u32x4_t kraw[4], vraw[4];
-    const uint32_t stride_b = (uint32_t)n_kv_heads * D * 2;  // bytes between tokens
+    constexpr uint32_t stride_b = D * 2;  // bytes between the tokens of a head plane
+    const int64_t plane = (int64_t)h * pool_tokens;  // first row of this kv head
     // K: token 16 hw + 4 i + b;  V: contraction slot 4 hw + j of group b = token 16 hw + 4 b + j
     const uint32_t k_lane_off = (uint32_t)(16 * hw + b) * stride_b + a * 16;
     const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + a * 16;
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         // cache policy of the loads: 2 = non-temporal, for rows that no other item reads
         constexpr int kAux = decltype(aux_tag)::value;
         if (sd.n > load_min) {
-            const int64_t base = (sd.tok * n_kv_heads + h) * (int64_t)D * 2;
+            const int64_t base = (plane + sd.tok) * (int64_t)D * 2;
             char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;  // uniform
             char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
             const int bytes = sd.n * (int)stride_b;
@@ -334,7 +336,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         };
         auto issue_unit = [&](int64_t tok, int n) {
             if (n > 0) {
-                const int64_t base = (tok * n_kv_heads + h) * (int64_t)D * 2;
+                const int64_t base = (plane + tok) * (int64_t)D * 2;
                 char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;
                 char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
                 const __amdgpu_buffer_rsrc_t kr =

@@ -18,6 +18,18 @@ def to_device(arr, device="cuda:0"):
     return torch.from_numpy(arr).to(device)
 
 
+def pool_to_device(arr, device="cuda:0"):
+    """K or V as the tests and the oracle index it, [pool row, kv head, D], laid out in
+    device memory the way the library reads it: [kv head][pool row][D]."""
+    return to_device(np.ascontiguousarray(arr.transpose(1, 0, 2)), device)
+
+
+def pool_to_host(t):
+    """Device pool [kv head][pool row][D] -> numpy view indexed [pool row, kv head, D]
+    (not copied again: the oracle takes the strides as they are)."""
+    return to_host_bits(t).transpose(1, 0, 2)
+
+
 def to_host_bits(t):
     """torch tensor -> numpy in the oracle's input convention."""
     if t.dtype == torch.bfloat16:
@@ -34,14 +46,14 @@ def make_ctx(cfg, options=None, device=0):
 
 
 def gpu_attn(ctx, tree, k_dev, v_dev, q_dev, mode=ets.ETS_PLAN_TREE, stream=None):
-    """Plans `tree`, runs one layer, returns (out [L,Hq,D], lse [L,Hq]) as torch tensors."""
+    """Plans `tree`, runs one layer on device pools [Hkv][pool_tokens][D], returns (out [L,Hq,D], lse [L,Hq]) as torch tensors."""
     st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node, mode)
     L, hq, d = tree.n_leaves, ctx.shape.n_q_heads, ctx.shape.head_dim
     dev = q_dev.device
     out = torch.full((L, hq, d), float("nan"), dtype=torch.float32, device=dev)
     lse = torch.full((L, hq), float("nan"), dtype=torch.float32, device=dev)
     ws = torch.empty(max(st.workspace_bytes, 16), dtype=torch.uint8, device=dev)
-    ctx.decode(k_dev, v_dev, k_dev.shape[0], q_dev, out, lse, ws, ws.numel(),
+    ctx.decode(k_dev, v_dev, k_dev.shape[1], q_dev, out, lse, ws, ws.numel(),
                None if stream is None else stream.cuda_stream)
     torch.cuda.synchronize()
     return out, lse, st

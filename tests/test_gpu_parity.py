@@ -11,8 +11,8 @@ import paper_2502_13575_amd as ets
 from workload import (CONFIGS, TreeConfig, make_tree, make_values_device, make_values_host,
                       random_tree)
 
-from _gpu_util import (compare, gpu_attn, make_ctx, oracle_full, oracle_rows, to_device,
-                       to_host_bits)
+from _gpu_util import (compare, gpu_attn, make_ctx, oracle_full, oracle_rows, pool_to_device,
+                       pool_to_host, to_device, to_host_bits)
 
 pytestmark = pytest.mark.gpu
 
@@ -30,7 +30,7 @@ def _run_full(cfg, tree, variant, what):
     k, v, q = make_values_host(cfg, tree)
     print("case", what, variant, flush=True)
     with make_ctx(cfg, options) as ctx:
-        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+        out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q), mode)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     d = cfg.head_dim
     return compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
@@ -59,7 +59,7 @@ def test_c4_sampled_parity(variant):
     k, v, q = make_values_host(cfg, tree)
     print("case c4", variant, flush=True)
     with make_ctx(cfg, options) as ctx:
-        out, lse, _ = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+        out, lse, _ = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q), mode)
     r = np.random.default_rng(4)
     leaves = r.integers(0, tree.n_leaves, size=192).astype(np.int32)
     heads = r.integers(0, cfg.n_q_heads, size=192).astype(np.int32)
@@ -81,7 +81,7 @@ def test_c5_two_layers_sampled_parity():
             out, lse, _ = gpu_attn(ctx, tree, kd[layer], vd[layer], qd[layer])
             leaves = r.integers(0, tree.n_leaves, size=48).astype(np.int32)
             heads = r.integers(0, cfg.n_q_heads, size=48).astype(np.int32)
-            k, v, q = to_host_bits(kd[layer]), to_host_bits(vd[layer]), to_host_bits(qd[layer])
+            k, v, q = pool_to_host(kd[layer]), pool_to_host(vd[layer]), to_host_bits(qd[layer])
             oo, ol = oracle_rows(cfg, tree, k, v, q, leaves, heads)
             compare(out.cpu().numpy()[leaves, heads], lse.cpu().numpy()[leaves, heads], oo, ol,
                     cfg.dtype, "c5/layer%d" % layer)
@@ -104,7 +104,7 @@ def test_fuzz_irregular_forests(seed):
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
         print("case fuzz", seed, mode, flush=True)
         with make_ctx(cfg, options) as ctx:
-            out, lse, _ = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q), mode)
+            out, lse, _ = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q), mode)
         compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
                 oo.reshape(-1, d), ol.reshape(-1), dt, "fuzz%d/mode%d" % (seed, mode))
 
@@ -112,7 +112,8 @@ def test_fuzz_irregular_forests(seed):
 def test_flat_equals_tree_and_runs_are_bitwise_reproducible():
     cfg = CONFIGS["c3_pruned"]
     tree = make_tree(cfg)
-    k, v, q = (to_device(x) for x in make_values_host(cfg, tree))
+    k, v, q = make_values_host(cfg, tree)
+    k, v, q = pool_to_device(k), pool_to_device(v), to_device(q)
     with make_ctx(cfg) as ctx:
         o1, l1, _ = gpu_attn(ctx, tree, k, v, q, ets.ETS_PLAN_TREE)
         o2, l2, _ = gpu_attn(ctx, tree, k, v, q, ets.ETS_PLAN_TREE)
@@ -134,7 +135,7 @@ def test_repeated_runs_bitwise_equal_on_ragged_paths(share):
                     np.zeros(8, np.int32), n)
         k, v, q = make_values_host(cfg, tree)
         oo, ol = oracle_full(cfg, tree, k, v, q)
-        kd, vd, qd = to_device(k), to_device(v), to_device(q)
+        kd, vd, qd = pool_to_device(k), pool_to_device(v), to_device(q)
         with make_ctx(cfg, opts) as ctx:
             runs = [gpu_attn(ctx, tree, kd, vd, qd) for _ in range(4)]
         for out, lse, _ in runs[1:]:
@@ -155,7 +156,7 @@ def test_edge_cases_empty_and_duplicate_leaves():
     q[1] = q[0]
     oo, ol = oracle_full(cfg, tree, k, v, q)
     with make_ctx(cfg) as ctx:
-        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q))
+        out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
         compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
                 oo.reshape(-1, 128), ol.reshape(-1), "bf16", "edge")
         assert torch.equal(out[0], out[1]) and torch.equal(lse[0], lse[1])
@@ -203,7 +204,7 @@ def test_long_chain_of_one_token_nodes():
     oo, ol = oracle_full(cfg, tree, k, v, q)
     print("case one-token chain", flush=True)
     with make_ctx(cfg) as ctx:
-        out, lse, st = gpu_attn(ctx, tree, to_device(k), to_device(v), to_device(q))
+        out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
     compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
             oo.reshape(-1, 128), ol.reshape(-1), "bf16", "chain")
 
@@ -218,7 +219,7 @@ def test_decode_loop_append_advance_attend(name, opts, steps):
     cfg = CONFIGS[name]
     tree = with_growth_room(make_tree(cfg), steps + 2)
     k, v, q = make_values_host(cfg, tree)
-    kd, vd, qd = to_device(k), to_device(v), to_device(q)
+    kd, vd, qd = pool_to_device(k), pool_to_device(v), to_device(q)
     n_tokens = tree.n_tokens.copy()
     L, hq, d = tree.n_leaves, cfg.n_q_heads, cfg.head_dim
     replans = 0
@@ -242,8 +243,7 @@ def test_decode_loop_append_advance_attend(name, opts, steps):
                 oo, ol = oracle_full(cfg, grown, k, v, q)
                 compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
                         oo.reshape(-1, d), ol.reshape(-1), cfg.dtype, "%s step %d" % (name, step))
-    from _gpu_util import to_host_bits
-    assert np.array_equal(to_host_bits(kd), k) and np.array_equal(to_host_bits(vd), v)
+    assert np.array_equal(pool_to_host(kd), k) and np.array_equal(pool_to_host(vd), v)
     if steps > 33 and opts.get("mfma", 1):
         assert replans >= 1
 

@@ -341,6 +341,32 @@ def test_rows_subset_equals_full():
         assert lse_s[i] == lse_f[sl[i], sh[i]]
 
 
+def test_memory_order_of_the_pool_does_not_matter():
+    # The same K[t, h, :] values held head-major in memory and handed over as a strided
+    # view give bit-identical results; with V of kv head h = constant h the view must
+    # still resolve heads by its second axis (a swapped stride would mix the constants).
+    r = np.random.default_rng(12)
+    t = random_tree(21, n_nodes=16, n_leaves=5, max_tokens=9, p_empty=0.0)
+    hkv, hq, d = 3, 6, 8
+    k = r.standard_normal((t.pool_tokens, hkv, d)).astype(np.float32)
+    v = r.standard_normal((t.pool_tokens, hkv, d)).astype(np.float32)
+    q = r.standard_normal((t.n_leaves, hq, d)).astype(np.float32)
+    out0, lse0 = _run(t, k, v, q, hkv, hq, d)
+    k_hm = np.ascontiguousarray(k.transpose(1, 0, 2))   # memory: [head][row][d]
+    v_hm = np.ascontiguousarray(v.transpose(1, 0, 2))
+    out1, lse1 = _run(t, k_hm.transpose(1, 0, 2), v_hm.transpose(1, 0, 2), q, hkv, hq, d)
+    assert np.array_equal(out0, out1) and np.array_equal(lse0, lse1)
+    vc = np.ascontiguousarray(np.broadcast_to(
+        np.arange(hkv, dtype=np.float32)[:, None, None], (hkv, t.pool_tokens, d)))
+    out2, _ = _run(t, k_hm.transpose(1, 0, 2), vc.transpose(1, 0, 2), q, hkv, hq, d)
+    want = (np.arange(hq) // (hq // hkv)).astype(np.float64)
+    assert np.allclose(out2, want[None, :, None], rtol=0, atol=1e-13)
+    o_p, m_p, l_p = oracle.partial(k_hm.transpose(1, 0, 2), v_hm.transpose(1, 0, 2),
+                                   q[0, 3].astype(np.float64), 1, np.arange(4))
+    o_c, m_c, l_c = oracle.partial(k, v, q[0, 3].astype(np.float64), 1, np.arange(4))
+    assert np.array_equal(o_p, o_c) and m_p == m_c and l_p == l_c
+
+
 # --------------------------------------------------------------- generator
 def test_bf16_bits_roundtrip_and_rne():
     x = np.array([1.0, 1.00390625, 1.005859375, -2.5, 3.140625, 1e-3], dtype=np.float32)

@@ -175,7 +175,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 def make_values_host(cfg: TreeConfig, tree: Tree, seed: Optional[int] = None,
                      layer: int = 0):
-    """K, V: [pool_tokens, Hkv, D]; Q: [L, Hq, D]; i.i.d. N(0,1).
+    """K, V indexed [pool row, kv head, D] (the device library wants them laid out
+    [kv head][pool row][D]: transpose before uploading); Q: [L, Hq, D]; i.i.d. N(0,1).
     float32 arrays for dtype "f32", uint16 bfloat16 bit patterns for "bf16"."""
     seed = cfg.seed if seed is None else seed
     r = _rng(seed, 2 + layer)
@@ -193,7 +194,8 @@ def make_values_host(cfg: TreeConfig, tree: Tree, seed: Optional[int] = None,
 def make_values_device(cfg: TreeConfig, tree: Tree, device, seed: Optional[int] = None,
                        layers: Optional[int] = None):
     """Device-side generation for pools too large to draw on the host.
-    Returns torch tensors K, V: [layers, pool_tokens, Hkv, D], Q: [layers, L, Hq, D]
+    Returns torch tensors K, V: [layers, Hkv, pool_tokens, D] (the library's memory
+    layout of a pool), Q: [layers, L, Hq, D]
     in cfg.dtype, drawn N(0,1) by torch's seeded device generator."""
     import torch
     seed = cfg.seed if seed is None else seed
@@ -201,7 +203,7 @@ def make_values_device(cfg: TreeConfig, tree: Tree, device, seed: Optional[int] 
     dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     g = torch.Generator(device=device)
     g.manual_seed(int(seed))
-    k = torch.empty((layers, tree.pool_tokens, cfg.n_kv_heads, cfg.head_dim),
+    k = torch.empty((layers, cfg.n_kv_heads, tree.pool_tokens, cfg.head_dim),
                     dtype=dt, device=device)
     v = torch.empty_like(k)
     q = torch.empty((layers, tree.n_leaves, cfg.n_q_heads, cfg.head_dim),
