@@ -58,6 +58,8 @@ def _load():
         lib.ets_oracle_attn.argtypes = common + [f64p, f64p]
         lib.ets_oracle_attn_rows.restype = C.c_int
         lib.ets_oracle_attn_rows.argtypes = common + [C.c_int64, i32p, i32p, f64p, f64p]
+        lib.ets_oracle_prefill_rows.restype = C.c_int
+        lib.ets_oracle_prefill_rows.argtypes = common + [C.c_int64, i32p, i32p, i32p, f64p, f64p]
         lib.ets_oracle_partial.restype = None
         lib.ets_oracle_partial.argtypes = [C.c_int32, C.c_int, C.c_double,
                                            C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
@@ -204,6 +206,82 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
     if rc:
         raise RuntimeError("oracle failed (code %d)" % rc)
     return out, lse
+
+
+def prefill_q_ptr(n_tokens, leaf_node):
+    """First query row of every leaf query in step prefill: int64 [L + 1], the prefix
+    sums of the leaf nodes' lengths (every token of a leaf query's node is a query)."""
+    lens = np.asarray(n_tokens, dtype=np.int64)[np.asarray(leaf_node, dtype=np.int64)]
+    return np.concatenate([np.zeros(1, np.int64), np.cumsum(lens, dtype=np.int64)])
+
+
+def tree_prefill_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
+                      n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
+    """Oracle step-prefill attention: token i of leaf query l's node sees every row of the
+    node's strict ancestors and rows 0..i of the node.  k_pool/v_pool as in
+    tree_decode_attn; q: [n_q_rows, Hq, D], rows ordered as prefill_q_ptr says.
+
+    rows=None: everything -> out float64 [n_q_rows, Hq, D], lse [n_q_rows, Hq].
+    rows=(leaf_idx, tok_idx, head_idx): only those triples -> out [n, D], lse [n].
+    """
+    k_pool, dt, ts, hs = _pool(k_pool)
+    v_pool, dt2, ts2, hs2 = _pool(v_pool)
+    if k_pool.shape != v_pool.shape or (ts2, hs2) != (ts, hs):
+        k_pool, dt, ts, hs = _pool(np.ascontiguousarray(k_pool))
+        v_pool, dt2, ts2, hs2 = _pool(np.ascontiguousarray(v_pool))
+    q, dt3 = _vals(q)
+    if not (dt == dt2 == dt3):
+        raise TypeError("k, v, q must share one dtype")
+    keep, targs = _tree_args(parent, tok_offset, n_tokens, leaf_node)
+    rc = check_tree(*keep, k_pool.shape[0])
+    if rc:
+        raise ValueError("oracle: malformed tree (code %d)" % rc)
+    q_ptr = prefill_q_ptr(keep[2], keep[3])
+    n_rows = int(q_ptr[-1])
+    assert k_pool.shape == v_pool.shape == (k_pool.shape[0], n_kv_heads, head_dim)
+    assert q.shape == (n_rows, n_q_heads, head_dim)
+    full = rows is None
+    if full:
+        L = keep[3].shape[0]
+        lens = np.diff(q_ptr)
+        sl = np.repeat(np.repeat(np.arange(L, dtype=np.int32), lens), n_q_heads)
+        st = np.repeat(np.concatenate([np.arange(n, dtype=np.int32) for n in lens] +
+                                      [np.zeros(0, np.int32)]), n_q_heads)
+        sh = np.tile(np.arange(n_q_heads, dtype=np.int32), n_rows)
+    else:
+        sl, st, sh = _i32(rows[0]), _i32(rows[1]), _i32(rows[2])
+    sl, st, sh = _i32(sl), _i32(st), _i32(sh)
+    n = sl.shape[0]
+    out = np.zeros((n, head_dim), dtype=np.float64)
+    lse = np.zeros((n,), dtype=np.float64)
+    common = targs + [n_kv_heads, n_q_heads, head_dim, dt, float(sm_scale),
+                      k_pool.ctypes.data_as(C.c_void_p), v_pool.ctypes.data_as(C.c_void_p),
+                      ts, hs, q.ctypes.data_as(C.c_void_p)]
+    rc = _load().ets_oracle_prefill_rows(*common, n, _p(sl, C.c_int32), _p(st, C.c_int32),
+                                         _p(sh, C.c_int32), _p(out, C.c_double),
+                                         _p(lse, C.c_double))
+    if rc:
+        raise RuntimeError("oracle failed (code %d)" % rc)
+    if full:
+        return out.reshape(n_rows, n_q_heads, head_dim), lse.reshape(n_rows, n_q_heads)
+    return out, lse
+
+
+def visible_rows(parent, tok_offset, n_tokens, node, own_rows=None):
+    """Pool rows a query on `node` sees, in path order: all rows of the strict ancestors,
+    then the first `own_rows` rows of the node (None: all of them)."""
+    chain = []
+    x = int(node)
+    while x >= 0:
+        chain.append(x)
+        x = int(parent[x])
+    chain.reverse()
+    rows = []
+    for n in chain[:-1]:
+        rows.extend(range(int(tok_offset[n]), int(tok_offset[n]) + int(n_tokens[n])))
+    own = int(n_tokens[node]) if own_rows is None else min(int(own_rows), int(n_tokens[node]))
+    rows.extend(range(int(tok_offset[node]), int(tok_offset[node]) + own))
+    return np.asarray(rows, dtype=np.int64)
 
 
 def partial(k_pool, v_pool, qvec, kv_head, rows, sm_scale=0.0):

@@ -26,6 +26,15 @@
  * so the attention formula is the standard scaled-dot-product one; the paper
  * supplies the tree and sharing semantics.
  *
+ * Step prefill (scoring a newly generated step with the reward model: the paper's
+ * search scores every candidate step, Abstract, Sec. 1 and Sec. 5.1; the reward
+ * model is a transformer with the same tree of cached steps): every token i of the
+ * leaf node v of a leaf query carries a query vector of its own; it sees all rows of
+ * v's strict ancestors and rows 0..i of v itself (causal inside the new step), and
+ * the same three formulas apply to that row set.  Query rows are numbered leaf query
+ * by leaf query: row q_ptr[l] + i with q_ptr[l] = sum of n_tokens[leaf_node[l']]
+ * over l' < l.
+ *
  * Also here, for pinning the identity the GPU path relies on: the partial
  * (unnormalised) result of an arbitrary token subset and the log-sum-exp merge
  * of several partials.
@@ -121,11 +130,13 @@ void ets_oracle_tree_stats(int32_t n_nodes, const int32_t* parent, const int32_t
     *live_nodes = live;
 }
 
-/* Attention of one (leaf, query head) over its whole path.  out has D entries. */
+/* Attention of query row q_row, query head j, over the path of node v: every row of v's
+ * strict ancestors and the first own_rows rows of v itself (own_rows < 0: all of them).
+ * out has D entries. */
 static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int32_t* n_tokens,
-                    int32_t v, int32_t Hkv, int32_t Hq, int32_t D, int dtype, double scale,
-                    const void* k_pool, const void* v_pool, int64_t tok_stride,
-                    int64_t head_stride, const void* q, int32_t leaf, int32_t j, double* out,
+                    int32_t v, int64_t own_rows, int32_t Hkv, int32_t Hq, int32_t D, int dtype,
+                    double scale, const void* k_pool, const void* v_pool, int64_t tok_stride,
+                    int64_t head_stride, const void* q, int64_t q_row, int32_t j, double* out,
                     double* lse) {
     const int32_t G = Hq / Hkv;
     const int32_t h = j / G;
@@ -135,8 +146,9 @@ static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int3
     int64_t k = depth;
     for (int32_t x = v; x >= 0; x = parent[x]) path[--k] = x;
 
-    int64_t n_p = 0;
-    for (int64_t i = 0; i < depth; ++i) n_p += n_tokens[path[i]];
+    if (own_rows < 0 || own_rows > n_tokens[v]) own_rows = n_tokens[v];
+    int64_t n_p = own_rows;
+    for (int64_t i = 0; i + 1 < depth; ++i) n_p += n_tokens[path[i]];
     for (int32_t d = 0; d < D; ++d) out[d] = 0.0;
     if (n_p == 0) {
         *lse = -INFINITY;
@@ -150,10 +162,12 @@ static int attn_one(const int32_t* parent, const int64_t* tok_offset, const int3
         return 1;
     }
     int64_t t = 0;
-    for (int64_t i = 0; i < depth; ++i)
-        for (int32_t r = 0; r < n_tokens[path[i]]; ++r) rows[t++] = tok_offset[path[i]] + r;
+    for (int64_t i = 0; i < depth; ++i) {
+        const int64_t n_vis = i + 1 < depth ? n_tokens[path[i]] : own_rows;
+        for (int64_t r = 0; r < n_vis; ++r) rows[t++] = tok_offset[path[i]] + r;
+    }
 
-    const int64_t qbase = ((int64_t)leaf * Hq + j) * D;
+    const int64_t qbase = (q_row * Hq + j) * D;
     double m = -INFINITY;
     for (t = 0; t < n_p; ++t) {
         const int64_t kbase = rows[t] * tok_stride + h * head_stride;
@@ -196,7 +210,7 @@ int ets_oracle_attn_rows(int32_t n_nodes, const int32_t* parent, const int64_t* 
             err = 3;
             continue;
         }
-        int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], Hkv, Hq, D, dtype, scale,
+        int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], -1, Hkv, Hq, D, dtype, scale,
                          k_pool, v_pool, tok_stride, head_stride, q, l, j, out + i * D, lse + i);
         if (e) {
 #pragma omp atomic write
@@ -220,13 +234,51 @@ int ets_oracle_attn(int32_t n_nodes, const int32_t* parent, const int64_t* tok_o
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t i = 0; i < n; ++i) {
         const int32_t l = (int32_t)(i / Hq), j = (int32_t)(i % Hq);
-        int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], Hkv, Hq, D, dtype, scale,
+        int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], -1, Hkv, Hq, D, dtype, scale,
                          k_pool, v_pool, tok_stride, head_stride, q, l, j, out + i * D, lse + i);
         if (e) {
 #pragma omp atomic write
             err = e;
         }
     }
+    return err;
+}
+
+/* Step prefill, selected (leaf query, token of its node, query head) triples:
+ * out [n_sel][D], lse [n_sel].  q is [sum of leaf node lengths][Hq][D]. */
+int ets_oracle_prefill_rows(int32_t n_nodes, const int32_t* parent, const int64_t* tok_offset,
+                            const int32_t* n_tokens, int32_t n_leaves, const int32_t* leaf_node,
+                            int32_t Hkv, int32_t Hq, int32_t D, int dtype, double scale,
+                            const void* k_pool, const void* v_pool, int64_t tok_stride,
+                            int64_t head_stride, const void* q, int64_t n_sel,
+                            const int32_t* sel_leaf, const int32_t* sel_tok,
+                            const int32_t* sel_head, double* out, double* lse) {
+    (void)n_nodes;
+    if (Hkv <= 0 || Hq % Hkv != 0 || D <= 0) return 2;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)D);
+    int64_t* q_ptr = (int64_t*)malloc(sizeof(int64_t) * ((size_t)n_leaves + 1));
+    if (!q_ptr) return 1;
+    q_ptr[0] = 0;
+    for (int32_t l = 0; l < n_leaves; ++l) q_ptr[l + 1] = q_ptr[l] + n_tokens[leaf_node[l]];
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_sel; ++i) {
+        const int32_t l = sel_leaf[i], tok = sel_tok[i], j = sel_head[i];
+        if (l < 0 || l >= n_leaves || j < 0 || j >= Hq || tok < 0 ||
+            tok >= n_tokens[leaf_node[l]]) {
+#pragma omp atomic write
+            err = 3;
+            continue;
+        }
+        int e = attn_one(parent, tok_offset, n_tokens, leaf_node[l], (int64_t)tok + 1, Hkv, Hq, D,
+                         dtype, scale, k_pool, v_pool, tok_stride, head_stride, q,
+                         q_ptr[l] + tok, j, out + i * D, lse + i);
+        if (e) {
+#pragma omp atomic write
+            err = e;
+        }
+    }
+    free(q_ptr);
     return err;
 }
 
