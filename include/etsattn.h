@@ -237,6 +237,65 @@ typedef struct {
 } ets_profile;
 ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out /* host */);
 
+/* ---- Step prefill: scoring a newly generated step with the reward model ----------
+ *
+ * The search scores every candidate step with a process reward model (ETS paper,
+ * Abstract; Sec. 1; Sec. 5.1: the PRM score at each step is that step's reward).  The
+ * reward model is a transformer over the same tree of cached steps, so scoring the
+ * steps just generated is a prefill of their tokens: EVERY token i of the node
+ * v = leaf_node[l] of leaf query l is a query; it sees all rows of v's strict
+ * ancestors and rows 0..i of v itself (causal inside the new step, whose K/V rows the
+ * caller has already written to the pools), and
+ *
+ *     lse[r,j] = ln sum_t exp(sm_scale * <q[r,j,:], K[t,h,:]>)     over the rows t it sees
+ *     out[r,j] = sum_t exp(s_t - lse[r,j]) * V[t,h,:],   h = j / (Hq/Hkv)
+ *
+ * where r = q_ptr[l] + i numbers the query rows leaf query by leaf query:
+ * q_ptr[l] = sum of n_tokens[leaf_node[l']] over l' < l (duplicate leaf queries on a
+ * node own separate rows; a node without tokens owns none).
+ *
+ * Built for bf16 pools with head_dim 128 (ETS_ERR_UNSUPPORTED otherwise).  The plan is
+ * separate from the decode plan of the same context; neither disturbs the other. */
+typedef struct {
+    int64_t n_leaves;
+    int64_t n_q_rows;          /* query rows = sum of the leaf queries' node lengths      */
+    int64_t n_items;           /* work items: blocks of rows_per_item / G query tokens    */
+    int64_t n_runs;            /* entries of the run lists on the device                  */
+    int64_t rows_per_item;     /* query rows (tokens x heads of a kv head) per work item  */
+    int64_t unique_tokens;     /* rows of the nodes on some leaf query's chain, once      */
+    int64_t unique_kv_bytes;   /* K plus V of those rows over all kv heads, one layer     */
+    int64_t streamed_tokens;   /* rows walked, summed over the work items                 */
+    int64_t streamed_kv_bytes; /* the same in bytes: what L2 and HBM serve together       */
+    int64_t visible_pairs;     /* (query token, visible row) pairs                        */
+    int64_t flops;             /* 4 * head_dim * n_q_heads * visible_pairs                */
+    int64_t min_pool_tokens;   /* pools must hold at least this many rows per head        */
+} ets_prefill_stats;
+
+/* Plans step prefill for `tree` (host arrays, borrowed for the call; same rules and
+ * errors as ets_plan).  Waits for the context's previous work before it replaces the
+ * device tables. */
+ets_status ets_plan_prefill(ets_ctx* ctx, const ets_tree* tree);
+ets_status ets_prefill_plan_stats(const ets_ctx* ctx, ets_prefill_stats* out /* host */);
+/* q_ptr: HOST, [n_leaves + 1], the first query row of every leaf query. */
+ets_status ets_prefill_q_ptr(const ets_ctx* ctx, int64_t* q_ptr);
+/* For checking the indexing bit for bit: the pool rows that query token `tok` of leaf
+ * query `leaf` sees according to the work items and their masks, in reading order.
+ * rows: HOST, capacity cap; *n_rows (may be NULL) receives the count; too small a cap
+ * or tok outside the node gives ETS_ERR_INVALID_ARG. */
+ets_status ets_prefill_cover(const ets_ctx* ctx, int32_t leaf, int32_t tok, int64_t* rows,
+                             int64_t cap, int64_t* n_rows);
+/* One layer of step-prefill attention.
+ *   k_pool, v_pool, pool_tokens   as in ets_tree_decode_attn
+ *   q     DEVICE, [n_q_rows][n_q_heads][head_dim] bf16, 16-byte aligned
+ *   out   DEVICE, [n_q_rows][n_q_heads][head_dim] float, 16-byte aligned
+ *   lse   DEVICE, [n_q_rows][n_q_heads] float
+ * Enqueues one kernel per 65535 work items on hip_stream; no workspace, no allocation,
+ * no synchronisation; bitwise reproducible.  ETS_ERR_NO_PLAN before ets_plan_prefill,
+ * ETS_ERR_HIP on a host-only context. */
+ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                 int64_t pool_tokens, const void* q, float* out, float* lse,
+                                 void* hip_stream);
+
 /* Static string for a status code. */
 const char* ets_strerror(int status);
 

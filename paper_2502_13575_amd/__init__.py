@@ -6,13 +6,16 @@ There is no CPU fallback; loading fails loudly when the library is not built.
 from .binding import (ETS_BF16, ETS_F32, ETS_PLAN_FLAT, ETS_PLAN_TREE, Context, EtsError,
                       EtsProfile, EtsShape, EtsStats, ets_create, ets_destroy, ets_plan, ets_plan_leaf_counts,
                       ets_plan_leaf_cover, ets_plan_paths, ets_plan_stats, ets_profile_read, ets_set_option,
-                      ets_kv_append, ets_plan_advance,
+                      ets_kv_append, ets_plan_advance, EtsPrefillStats, ets_plan_prefill,
+                      ets_prefill_plan_stats, ets_prefill_q_ptr, ets_prefill_cover,
+                      ets_tree_prefill_attn,
                       ets_strerror, ets_tree_decode_attn, library_path, load_library)
 
 __all__ = [
     "ETS_BF16", "ETS_F32", "ETS_PLAN_FLAT", "ETS_PLAN_TREE", "Context", "EtsError", "EtsShape",
     "EtsStats", "EtsProfile", "ets_profile_read", "ets_create", "ets_destroy", "ets_plan", "ets_plan_leaf_counts",
     "ets_plan_leaf_cover", "ets_plan_paths", "ets_plan_stats", "ets_set_option", "ets_strerror",
-    "ets_kv_append", "ets_plan_advance",
+    "ets_kv_append", "ets_plan_advance", "EtsPrefillStats", "ets_plan_prefill",
+    "ets_prefill_plan_stats", "ets_prefill_q_ptr", "ets_prefill_cover", "ets_tree_prefill_attn",
     "ets_tree_decode_attn", "library_path", "load_library",
 ]

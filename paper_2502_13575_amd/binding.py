@@ -43,6 +43,16 @@ class EtsStats(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+class EtsPrefillStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "n_leaves", "n_q_rows", "n_items", "n_runs", "rows_per_item", "unique_tokens",
+        "unique_kv_bytes", "streamed_tokens", "streamed_kv_bytes", "visible_pairs", "flops",
+        "min_pool_tokens")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
 class EtsProfile(C.Structure):
     _fields_ = [("calls", C.c_int64), ("stream_ms", C.c_double), ("cascade_ms", C.c_double),
                 ("merge_ms", C.c_double)]
@@ -86,6 +96,16 @@ def load_library():
     lib.ets_kv_append.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
     lib.ets_plan_advance.restype = C.c_int
     lib.ets_plan_advance.argtypes = [vp, vp, i32p]
+    lib.ets_plan_prefill.restype = C.c_int
+    lib.ets_plan_prefill.argtypes = [vp, C.POINTER(_EtsTree)]
+    lib.ets_prefill_plan_stats.restype = C.c_int
+    lib.ets_prefill_plan_stats.argtypes = [vp, C.POINTER(EtsPrefillStats)]
+    lib.ets_prefill_q_ptr.restype = C.c_int
+    lib.ets_prefill_q_ptr.argtypes = [vp, i64p]
+    lib.ets_prefill_cover.restype = C.c_int
+    lib.ets_prefill_cover.argtypes = [vp, C.c_int32, C.c_int32, i64p, C.c_int64, i64p]
+    lib.ets_tree_prefill_attn.restype = C.c_int
+    lib.ets_tree_prefill_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp]
     lib.ets_profile_read.restype = C.c_int
     lib.ets_profile_read.argtypes = [vp, C.POINTER(EtsProfile)]
     lib.ets_strerror.restype = C.c_char_p
@@ -126,7 +146,8 @@ def ets_set_option(ctx, key: str, value: int):
     _check(load_library().ets_set_option(ctx, key.encode(), int(value)), "ets_set_option")
 
 
-def ets_plan(ctx, parent, tok_offset, n_tokens, leaf_node, mode: int = ETS_PLAN_TREE):
+def _tree_struct(parent, tok_offset, n_tokens, leaf_node):
+    """(_EtsTree, arrays to keep alive) from host arrays."""
     parent = np.ascontiguousarray(parent, dtype=np.int32)
     tok_offset = np.ascontiguousarray(tok_offset, dtype=np.int64)
     n_tokens = np.ascontiguousarray(n_tokens, dtype=np.int32)
@@ -137,7 +158,55 @@ def ets_plan(ctx, parent, tok_offset, n_tokens, leaf_node, mode: int = ETS_PLAN_
                  tok_offset.ctypes.data_as(C.POINTER(C.c_int64)),
                  n_tokens.ctypes.data_as(C.POINTER(C.c_int32)), leaf_node.shape[0],
                  leaf_node.ctypes.data_as(C.POINTER(C.c_int32)))
+    return t, (parent, tok_offset, n_tokens, leaf_node)
+
+
+def ets_plan(ctx, parent, tok_offset, n_tokens, leaf_node, mode: int = ETS_PLAN_TREE):
+    t, keep = _tree_struct(parent, tok_offset, n_tokens, leaf_node)
     _check(load_library().ets_plan(ctx, C.byref(t), int(mode)), "ets_plan")
+    del keep
+
+
+def ets_plan_prefill(ctx, parent, tok_offset, n_tokens, leaf_node):
+    t, keep = _tree_struct(parent, tok_offset, n_tokens, leaf_node)
+    _check(load_library().ets_plan_prefill(ctx, C.byref(t)), "ets_plan_prefill")
+    del keep
+
+
+def ets_prefill_plan_stats(ctx) -> EtsPrefillStats:
+    st = EtsPrefillStats()
+    _check(load_library().ets_prefill_plan_stats(ctx, C.byref(st)), "ets_prefill_plan_stats")
+    return st
+
+
+def ets_prefill_q_ptr(ctx):
+    """int64 [L + 1]: first query row of every leaf query."""
+    st = ets_prefill_plan_stats(ctx)
+    q_ptr = np.zeros(st.n_leaves + 1, dtype=np.int64)
+    _check(load_library().ets_prefill_q_ptr(ctx, q_ptr.ctypes.data_as(C.POINTER(C.c_int64))),
+           "ets_prefill_q_ptr")
+    return q_ptr
+
+
+def ets_prefill_cover(ctx, leaf: int, tok: int):
+    """Pool rows (int64 [n]) that query token `tok` of leaf query `leaf` sees, in reading order."""
+    lib = load_library()
+    n = C.c_int64(0)
+    rc = lib.ets_prefill_cover(ctx, int(leaf), int(tok), None, 0, C.byref(n))
+    if rc != 0 and not (rc == 1 and n.value > 0):
+        _check(rc, "ets_prefill_cover")
+    rows = np.zeros(max(n.value, 1), dtype=np.int64)
+    _check(lib.ets_prefill_cover(ctx, int(leaf), int(tok),
+                                 rows.ctypes.data_as(C.POINTER(C.c_int64)), rows.shape[0],
+                                 C.byref(n)), "ets_prefill_cover")
+    return rows[:n.value].copy()
+
+
+def ets_tree_prefill_attn(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse, hip_stream=None):
+    stream = None if hip_stream is None else C.c_void_p(int(hip_stream))
+    _check(load_library().ets_tree_prefill_attn(
+        ctx, _dev_ptr(k_pool), _dev_ptr(v_pool), int(pool_tokens), _dev_ptr(q), _dev_ptr(out),
+        _dev_ptr(lse), stream), "ets_tree_prefill_attn")
 
 
 def ets_plan_stats(ctx) -> EtsStats:
@@ -266,6 +335,22 @@ class Context:
 
     def profile_read(self) -> EtsProfile:
         return ets_profile_read(self._ctx)
+
+    def plan_prefill(self, parent, tok_offset, n_tokens, leaf_node) -> EtsPrefillStats:
+        ets_plan_prefill(self._ctx, parent, tok_offset, n_tokens, leaf_node)
+        return ets_prefill_plan_stats(self._ctx)
+
+    def prefill_stats(self) -> EtsPrefillStats:
+        return ets_prefill_plan_stats(self._ctx)
+
+    def prefill_q_ptr(self):
+        return ets_prefill_q_ptr(self._ctx)
+
+    def prefill_cover(self, leaf, tok):
+        return ets_prefill_cover(self._ctx, leaf, tok)
+
+    def prefill(self, k_pool, v_pool, pool_tokens, q, out, lse, hip_stream=None):
+        ets_tree_prefill_attn(self._ctx, k_pool, v_pool, pool_tokens, q, out, lse, hip_stream)
 
     def decode(self, k_pool, v_pool, pool_tokens, q, out, lse, workspace, workspace_bytes,
                hip_stream=None):

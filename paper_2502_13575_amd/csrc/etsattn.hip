@@ -11,6 +11,8 @@
 #include "etsattn.h"
 #include "merge_kernel.hpp"
 #include "plan.h"
+#include "prefill_attn_kernel.hpp"
+#include "prefill_plan.h"
 #include "stream_kernel.hpp"
 #include "tree_attn_kernel.hpp"
 
@@ -34,6 +36,12 @@ struct ets_ctx {
     AdvEntry* d_adv = nullptr;       // decode-step advance: tails to extend
     int32_t* d_adv_src = nullptr;    // per growing node: leaf query that supplies its new token
     int64_t* d_adv_row0 = nullptr;   // per growing node: first free pool row at plan time
+    // step prefill: its own plan and device tables
+    PrefillPlan prefill;
+    char* d_pre_buf = nullptr;
+    size_t d_pre_cap = 0;
+    Run* d_pre_runs = nullptr;
+    PrefillItem* d_pre_items = nullptr;
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
     // kernel timing (benchmarks only): four events per recorded call
@@ -190,6 +198,40 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     }
 }
 
+ets_status upload_prefill_plan(ets_ctx* c) {
+    const PrefillPlan& p = c->prefill;
+    // the kernel's prologue reads a whole descriptor per thread only below n_runs, but
+    // keep the table padded so that a wide scalar load near its end stays inside
+    const size_t b_runs = align_up((p.runs.size() + 4) * sizeof(Run), 256);
+    const size_t b_items = align_up(p.items.size() * sizeof(PrefillItem), 256);
+    const size_t total = b_runs + b_items + 256;
+    std::vector<char> stage(total, 0);
+    if (!p.runs.empty()) std::memcpy(stage.data(), p.runs.data(), p.runs.size() * sizeof(Run));
+    if (!p.items.empty())
+        std::memcpy(stage.data() + b_runs, p.items.data(), p.items.size() * sizeof(PrefillItem));
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    if (c->stream_used && hipStreamSynchronize(c->last_stream) != hipSuccess) return ETS_ERR_HIP;
+    if (total > c->d_pre_cap) {
+        if (c->d_pre_buf) (void)hipFree(c->d_pre_buf);
+        c->d_pre_buf = nullptr;
+        c->d_pre_cap = 0;
+        const size_t want = align_up(total + total / 2, 4096);
+        if (hipMalloc(reinterpret_cast<void**>(&c->d_pre_buf), want) != hipSuccess) {
+            (void)hipGetLastError();
+            return ETS_ERR_HIP;
+        }
+        c->d_pre_cap = want;
+    }
+    if (hipMemcpy(c->d_pre_buf, stage.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        return ETS_ERR_HIP;
+    }
+    c->d_pre_runs = reinterpret_cast<Run*>(c->d_pre_buf);
+    c->d_pre_items = reinterpret_cast<PrefillItem*>(c->d_pre_buf + b_runs);
+    return ETS_OK;
+}
+
 constexpr size_t kMaxProfiledCalls = 8192;
 
 // Event `which` (0..3) of the call being recorded, created on first use.
@@ -263,11 +305,12 @@ ets_status ets_create(ets_ctx** out, const ets_shape* shape, int hip_device) {
 
 void ets_destroy(ets_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->d_buf) {
+    if (ctx->d_buf || ctx->d_pre_buf) {
         DeviceGuard guard(ctx->device);
         if (guard.ok) {
             if (ctx->stream_used) (void)hipStreamSynchronize(ctx->last_stream);
-            (void)hipFree(ctx->d_buf);
+            if (ctx->d_buf) (void)hipFree(ctx->d_buf);
+            if (ctx->d_pre_buf) (void)hipFree(ctx->d_pre_buf);
         }
     }
     if (!ctx->events.empty()) {
@@ -469,6 +512,86 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
     (void)hipGetLastError();
     launch_all(ctx, a);
     ctx->last_stream = a.stream;
+    ctx->stream_used = true;
+    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    return ETS_OK;
+}
+
+ets_status ets_plan_prefill(ets_ctx* ctx, const ets_tree* tree) {
+    if (!ctx || !tree) return ETS_ERR_INVALID_ARG;
+    if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
+    ets_status s = build_prefill_plan(ctx->shape, *tree, ctx->prefill);
+    if (s != ETS_OK) return s;
+    if (ctx->device >= 0) {
+        s = upload_prefill_plan(ctx);
+        if (s != ETS_OK) ctx->prefill.valid = false;
+    }
+    return s;
+}
+
+ets_status ets_prefill_plan_stats(const ets_ctx* ctx, ets_prefill_stats* out) {
+    if (!ctx || !out) return ETS_ERR_INVALID_ARG;
+    if (!ctx->prefill.valid) return ETS_ERR_NO_PLAN;
+    *out = ctx->prefill.stats;
+    return ETS_OK;
+}
+
+ets_status ets_prefill_q_ptr(const ets_ctx* ctx, int64_t* q_ptr) {
+    if (!ctx || !q_ptr) return ETS_ERR_INVALID_ARG;
+    if (!ctx->prefill.valid) return ETS_ERR_NO_PLAN;
+    std::memcpy(q_ptr, ctx->prefill.q_ptr.data(), ctx->prefill.q_ptr.size() * sizeof(int64_t));
+    return ETS_OK;
+}
+
+ets_status ets_prefill_cover(const ets_ctx* ctx, int32_t leaf, int32_t tok, int64_t* rows,
+                             int64_t cap, int64_t* n_rows) {
+    if (!ctx || cap < 0 || (cap > 0 && !rows)) return ETS_ERR_INVALID_ARG;
+    if (!ctx->prefill.valid) return ETS_ERR_NO_PLAN;
+    const PrefillPlan& p = ctx->prefill;
+    if (leaf < 0 || leaf >= p.stats.n_leaves) return ETS_ERR_BAD_LEAF;
+    if (tok < 0 || tok >= p.n_tokens[p.leaf_node[leaf]]) return ETS_ERR_INVALID_ARG;
+    try {
+        std::vector<int64_t> r;
+        const bool ok = prefill_cover(p, leaf, tok, r);
+        if (n_rows) *n_rows = (int64_t)r.size();
+        if (!ok) return ETS_ERR_BAD_TREE;
+        if ((int64_t)r.size() > cap) return ETS_ERR_INVALID_ARG;
+        if (!r.empty()) std::memcpy(rows, r.data(), r.size() * sizeof(int64_t));
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+    return ETS_OK;
+}
+
+ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                 int64_t pool_tokens, const void* q, float* out, float* lse,
+                                 void* hip_stream) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->prefill.valid) return ETS_ERR_NO_PLAN;
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    const ets_prefill_stats& st = ctx->prefill.stats;
+    if (st.n_q_rows == 0) return ETS_OK;
+    if (!q || !out || !lse || !k_pool || !v_pool || pool_tokens < 0) return ETS_ERR_INVALID_ARG;
+    if (pool_tokens < st.min_pool_tokens) return ETS_ERR_BAD_TREE;
+    if (misaligned(k_pool) || misaligned(v_pool) || misaligned(q) || misaligned(out) ||
+        (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return ETS_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    const int g = ctx->shape.n_q_heads / ctx->shape.n_kv_heads;
+    const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    // grid: x = kv head, y = item, at most 65535 items per launch
+    for (int64_t y0 = 0; y0 < st.n_items; y0 += 65535) {
+        const unsigned ny = (unsigned)std::min<int64_t>(65535, st.n_items - y0);
+        hipLaunchKernelGGL(prefill_attn_kernel, dim3((unsigned)ctx->shape.n_kv_heads, ny), dim3(256),
+                           0, stream, static_cast<const bf16_t*>(k_pool),
+                           static_cast<const bf16_t*>(v_pool), pool_tokens,
+                           static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items, (int)y0,
+                           g_shift, ctx->scale * 1.4426950408889634f, out, lse);
+    }
+    ctx->last_stream = stream;
     ctx->stream_used = true;
     if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
     return ETS_OK;

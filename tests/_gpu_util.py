@@ -92,3 +92,23 @@ def oracle_rows(cfg, tree, k, v, q, leaves, heads):
     return oracle.tree_decode_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
                                    k, v, q, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim,
                                    rows=(leaves, heads))
+
+
+def gpu_prefill(ctx, tree, k_dev, v_dev, q_dev, stream=None):
+    """Plans step prefill for `tree`, runs one layer on device pools [Hkv][pool_tokens][D];
+    returns (out [n_q_rows, Hq, D], lse [n_q_rows, Hq]) as torch tensors and the stats."""
+    st = ctx.plan_prefill(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+    hq, d = ctx.shape.n_q_heads, ctx.shape.head_dim
+    dev = q_dev.device
+    out = torch.full((st.n_q_rows, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((st.n_q_rows, hq), float("nan"), dtype=torch.float32, device=dev)
+    ctx.prefill(k_dev, v_dev, k_dev.shape[1], q_dev, out, lse,
+                None if stream is None else stream.cuda_stream)
+    torch.cuda.synchronize()
+    return out, lse, st
+
+
+def oracle_prefill(cfg, tree, k, v, q, rows=None):
+    return oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                    k, v, q, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim,
+                                    rows=rows)

@@ -241,3 +241,16 @@ def make_new_tokens_host(cfg: TreeConfig, tree: Tree, step: int, seed: Optional[
     if cfg.dtype == "bf16":
         return to_bf16_bits(k), to_bf16_bits(v)
     return k, v
+
+
+def make_prefill_queries_host(cfg: TreeConfig, tree: Tree, seed: Optional[int] = None):
+    """Query vectors for step prefill: one row per token of every leaf query's node,
+    leaf query by leaf query, [sum of those node lengths, Hq, D], i.i.d. N(0,1), in the
+    pool's dtype convention."""
+    seed = cfg.seed if seed is None else seed
+    r = _rng(seed, 500)
+    n_rows = int(tree.n_tokens[tree.leaf_node].sum()) if tree.n_leaves else 0
+    q = r.standard_normal((n_rows, cfg.n_q_heads, cfg.head_dim), dtype=np.float32)
+    if cfg.dtype == "bf16":
+        return to_bf16_bits(q)
+    return q
