@@ -18,6 +18,7 @@ import time
 import numpy as np
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 / fp16 matrix-core peak, published
 
 
 def measured_traffic(workload):
@@ -76,6 +77,8 @@ def main():
     ap.add_argument("--option", action="append", default=[], help="planner knob key=value")
     ap.add_argument("--decode-tokens", type=int, default=8,
                     help="decode tokens of the append/advance measurement on one extra pool (0 = skip)")
+    ap.add_argument("--prefill-layers", type=int, default=4,
+                    help="timed layers of step-prefill attention on the same tree (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "scaling hardware byte counters when profiling)")
@@ -263,6 +266,54 @@ def main():
                                                       n_nodes, decode_step["append_GBps"]))
         del kr, vr, ws
 
+    prefill = None
+    pre_check = None
+    if args.prefill_layers > 0 and cfg.dtype == "bf16" and d == 128:
+        # Step prefill (scoring the leaf steps with a reward model of this shape): every
+        # token of every leaf node is a query.  Matrix-core bound: flops = 4 D Hq x
+        # (query token, visible row) pairs, against the dense bf16/fp16 MFMA peak.
+        t0 = time.perf_counter()
+        pst = ctx.plan_prefill(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        plan_p_ms = (time.perf_counter() - t0) * 1e3
+        nq = pst.n_q_rows
+        gq = torch.Generator(device=dev)
+        gq.manual_seed(cfg.seed + 77)
+        qp = torch.empty((nq, hq, d), dtype=torch.bfloat16, device=dev)
+        qp.normal_(generator=gq)
+        outp = torch.empty((nq, hq, d), dtype=torch.float32, device=dev)
+        lsep = torch.empty((nq, hq), dtype=torch.float32, device=dev)
+        ctx.prefill(kd[0], vd[0], tree.pool_tokens, qp, outp, lsep, stream.cuda_stream)
+        torch.cuda.synchronize()
+        if args.cpu_seconds > 0:
+            pre_check = (qp, outp.clone(), lsep.clone())
+        n_l = args.prefill_layers
+        evp = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_l)]
+        for i in range(n_l):
+            evp[2 * i].record(stream)
+            ctx.prefill(kd[(i + 1) % n_pools], vd[(i + 1) % n_pools], tree.pool_tokens, qp, outp,
+                        lsep, stream.cuda_stream)
+            evp[2 * i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms_l = sum(evp[2 * i].elapsed_time(evp[2 * i + 1]) for i in range(n_l)) / n_l
+        tflops = pst.flops / (ms_l * 1e-3) / 1e12
+        prefill = {"layers_timed": n_l, "q_rows": int(nq), "work_items": int(pst.n_items),
+                   "plan_ms": round(plan_p_ms, 3), "ms_per_layer": round(ms_l, 3),
+                   "query_tokens_per_s": round(nq / (ms_l * 1e-3), 1),
+                   "flops_per_layer": int(pst.flops),
+                   "unique_kv_bytes": int(pst.unique_kv_bytes),
+                   "streamed_kv_bytes": int(pst.streamed_kv_bytes),
+                   "roofline": {"bound": "mfma", "kernel": "prefill_attn_kernel",
+                                "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                                "traffic": None, "avg_launch_us": round(ms_l * 1e3, 1)}}
+        log("step prefill: %d query tokens, %.1f TFLOP per layer, %.2f ms per layer = "
+            "%.0f TFLOP/s (%.1f%% of the %d TFLOP/s matrix-core peak)" %
+            (nq, pst.flops / 1e12, ms_l, tflops, tflops / MFMA_PEAK_TFLOPS * 100,
+             MFMA_PEAK_TFLOPS))
+        if pre_check is None:
+            del qp
+        del outp, lsep
+
     cpu = None
     parity = None
     if args.cpu_seconds > 0:
@@ -307,6 +358,24 @@ def main():
                   "ok": bool(err_o <= tol and err_l <= tol)}
         log("oracle: %d rows in %.1f s on %d threads; parity out %.2e lse %.2e" %
             (n_rows, t_or, nthr, err_o, err_l))
+        if pre_check is not None:
+            qp, outp0, lsep0 = pre_check
+            qph = qp.view(torch.int16).cpu().numpy().view(np.uint16)
+            n_s = 4 * nthr
+            sl = r.integers(0, L, size=n_s).astype(np.int32)
+            stok = (r.random(n_s) * tree.n_tokens[tree.leaf_node[sl]]).astype(np.int32)
+            sh = r.integers(0, hq, size=n_s).astype(np.int32)
+            po, pl = oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens,
+                                              tree.leaf_node, kh, vh, qph, cfg.n_kv_heads, hq, d,
+                                              rows=(sl, stok, sh))
+            rows_ = oracle.prefill_q_ptr(tree.n_tokens, tree.leaf_node)[sl] + stok
+            ri = torch.from_numpy(rows_).to(dev)
+            hi = torch.from_numpy(sh.astype(np.int64)).to(dev)
+            e_o = float(np.abs(outp0[ri, hi].cpu().numpy().astype(np.float64) - po).max())
+            e_l = float(np.abs(lsep0[ri, hi].cpu().numpy().astype(np.float64) - pl).max())
+            prefill["parity_sample"] = {"rows": n_s, "out_max_abs": e_o, "lse_max_abs": e_l,
+                                        "tol_abs": tol, "ok": bool(e_o <= tol and e_l <= tol)}
+            log("oracle (prefill): %d rows; parity out %.2e lse %.2e" % (n_s, e_o, e_l))
 
     line = {
         "metric": "tree-decode attn leaf-queries/s (unique-KV HBM GB/s as % of peak alongside)",
@@ -338,6 +407,7 @@ def main():
         "cpu_baseline": cpu,
         "flat_baseline": flat,
         "decode_step": decode_step,
+        "prefill": prefill,
         "parity_sample": parity,
         "paper_context": "ETS reports 1.8x smaller KV and 1.4x search throughput vs REBASE on "
                          "2x H100 NVL with stock kernels; no kernel-level numbers",

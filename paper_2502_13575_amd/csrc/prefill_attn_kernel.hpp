@@ -37,73 +37,110 @@
 
 namespace ets {
 
-constexpr int kPrefillBlocksPerWave = 2;
+constexpr int kPrefillBlocksPerWave = 2;  // prefill_step is written for two
 
-// One run of 32 staged rows against the wave's NB blocks of 16 query rows.
-// lim[nb]: rows of the run that the lane's query row of block nb sees (may be <= 0).
-template <int NB, bool MASK>
+// Softmax pieces of one block of 16 query rows against one run of 32 rows.  Lane (a, b)
+// holds query row a against rows 4 b + i (s0) and 16 + 4 b + i (s1) of the run.
+// Masks the rows the query does not see (lim = rows of the run it sees, may be <= 0) and
+// returns the lane's largest score.
+__device__ __forceinline__ float prefill_mask_max(f32x4_t& s0, f32x4_t& s1, int b, int lim) {
+    const int rem = lim - 4 * b;  // row 4 b + i counts iff i < rem, row 16 + 4 b + i iff 16 + i < rem
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s0[i] = i < rem ? s0[i] : -INFINITY;
+        s1[i] = 16 + i < rem ? s1[i] : -INFINITY;
+    }
+    return fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                 fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+}
+
+// Raises the block's reference score when a score exceeds it by more than the margin.
+__device__ __forceinline__ void prefill_raise(float mx, float& m, float& lsum, f32x4_t (&oacc)[8],
+                                              float scale_log2e, float raise_margin) {
+    if (__any(mx > m + raise_margin)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2((m - m_new) * scale_log2e);
+        lsum *= alpha;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) oacc[x] *= alpha;
+        m = m_new;
+    }
+}
+
+// Weights of the masked scores against the reference, rounded to fp16 for the P V product.
+__device__ __forceinline__ f16x8_t prefill_weights(const f32x4_t& s0, const f32x4_t& s1, float m,
+                                                   float& lsum, float scale_log2e) {
+    const float mc = m * scale_log2e;
+    f16x8_t pf;
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float p0 = fast_exp2(fmaf(s0[i], scale_log2e, -mc));
+        const float p1 = fast_exp2(fmaf(s1[i], scale_log2e, -mc));
+        psum += p0 + p1;
+        pf[i] = (_Float16)p0;
+        pf[4 + i] = (_Float16)p1;
+    }
+    lsum += psum;
+    return pf;
+}
+
+// n groups of one matrix instruction followed by `valu` vector-ALU instructions: the
+// order in which the surrounding basic block is to be issued, so that a block's softmax
+// arithmetic runs while the matrix pipe works on the other block.
+template <int N, int VALU>
+__device__ __forceinline__ void interleave_mfma_valu() {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);  // VALU
+    }
+}
+
+// One run of 32 staged rows against the wave's two blocks of 16 query rows.  The two
+// blocks are independent, so their phases are staggered: while the matrix pipe computes
+// the scores of block 1 the vector ALU turns block 0's scores into weights, and while it
+// applies block 0's weights to V the vector ALU does the same for block 1.  K and V
+// fragments are read from LDS once per block (LDS bandwidth is not what limits here).
 __device__ __forceinline__ void prefill_step(const u32x4_t* __restrict__ ks_lane,
                                              const u32x4_t* __restrict__ vs_lane, int b,
-                                             const int (&lim)[NB], const bf16x8_t (&qf)[NB][4],
-                                             f32x4_t (&oacc)[NB][8], float (&m)[NB],
-                                             float (&lsum)[NB], float scale_log2e,
-                                             float raise_margin) {
+                                             const int (&lim)[2], const bf16x8_t (&qf)[2][4],
+                                             f32x4_t (&oacc)[2][8], float (&m)[2], float (&lsum)[2],
+                                             float scale_log2e, float raise_margin) {
     constexpr int KROW = kTreeAttnKRow;
-    f32x4_t s0[NB], s1[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        s0[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        s1[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    }
+    f32x4_t s0a = {0.f, 0.f, 0.f, 0.f}, s1a = s0a, s0b = s0a, s1b = s0a;
+    // scores of block 0
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8_t k0 = as_bf16x8(ks_lane[4 * kk]);
-        const bf16x8_t k1 = as_bf16x8(ks_lane[16 * KROW + 4 * kk]);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            s0[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[nb][kk], s0[nb], 0, 0, 0);
-            s1[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[nb][kk], s1[nb], 0, 0, 0);
-        }
+        s0a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[4 * kk]), qf[0][kk], s0a, 0, 0, 0);
+        s1a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[16 * KROW + 4 * kk]), qf[0][kk],
+                                                      s1a, 0, 0, 0);
     }
-    f16x8_t pf[NB];
+    const float mxa = prefill_mask_max(s0a, s1a, b, lim[0]);
+    prefill_raise(mxa, m[0], lsum[0], oacc[0], scale_log2e, raise_margin);
+    // scores of block 1 || weights of block 0
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        float s[8] = {s0[nb][0], s0[nb][1], s0[nb][2], s0[nb][3],
-                      s1[nb][0], s1[nb][1], s1[nb][2], s1[nb][3]};
-        if constexpr (MASK) {
-            const int rem = lim[nb] - 4 * b;  // rows 4 b + i count iff i < rem, 16 + 4 b + i iff i < rem - 16
-#pragma unroll
-            for (int j = 0; j < 8; ++j) s[j] = (16 * (j >> 2) + (j & 3)) < rem ? s[j] : -INFINITY;
-        }
-        float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
-                         fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-        if (__any(mx > m[nb] + raise_margin)) {
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m[nb], mx);
-            const float alpha = fast_exp2((m[nb] - m_new) * scale_log2e);
-            lsum[nb] *= alpha;
-#pragma unroll
-            for (int x = 0; x < 8; ++x) oacc[nb][x] *= alpha;
-            m[nb] = m_new;
-        }
-        const float mc = m[nb] * scale_log2e;
-        float psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(fmaf(s[j], scale_log2e, -mc));
-            psum += p;
-            pf[nb][j] = (_Float16)p;
-        }
-        lsum[nb] += psum;
+    for (int kk = 0; kk < 4; ++kk) {
+        s0b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[4 * kk]), qf[1][kk], s0b, 0, 0, 0);
+        s1b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[16 * KROW + 4 * kk]), qf[1][kk],
+                                                      s1b, 0, 0, 0);
     }
+    const f16x8_t pfa = prefill_weights(s0a, s1a, m[0], lsum[0], scale_log2e);
+    interleave_mfma_valu<8, 4>();
+    const float mxb = prefill_mask_max(s0b, s1b, b, lim[1]);
+    prefill_raise(mxb, m[1], lsum[1], oacc[1], scale_log2e, raise_margin);
+    // P V of block 0 || weights of block 1
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-        const f16x8_t vf = as_f16x8(vs_lane[x * 64]);
+    for (int x = 0; x < 8; ++x)
+        oacc[0][x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vs_lane[x * 64]), pfa, oacc[0][x], 0, 0, 0);
+    const f16x8_t pfb = prefill_weights(s0b, s1b, m[1], lsum[1], scale_log2e);
+    interleave_mfma_valu<8, 4>();
+    // P V of block 1
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            oacc[nb][x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf[nb], oacc[nb][x], 0, 0, 0);
-    }
+    for (int x = 0; x < 8; ++x)
+        oacc[1][x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vs_lane[x * 64]), pfb, oacc[1][x], 0, 0, 0);
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attn_kernel(
@@ -253,20 +290,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void p
             const u32x4_t d = sm_desc[sidx & (RING - 1)];
             const int n_valid = __builtin_amdgcn_readfirstlane(d[2]);
             const int kpos = __builtin_amdgcn_readfirstlane(d[3]);
-            if (kpos > i_hi) continue;  // none of the wave's rows sees this run
             const u32x4_t* ks_lane = ks + (32 * st + a) * KROW + b;
             const u32x4_t* vs_lane = vs + st * 8 * 64 + lane;
-            if (n_valid < 32 || kpos + 31 > i_lo) {
-                int lim[NB];
+            // one code path for every run (the accumulators stay in place): the mask is
+            // always applied, a run that needs none has lim = 32
+            int lim[NB];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) lim[nb] = min(n_valid, i_row[nb] - kpos + 1);
-                prefill_step<NB, true>(ks_lane, vs_lane, b, lim, qf, oacc, m, lsum, scale_log2e,
-                                       raise_margin);
-            } else {
-                const int lim[NB] = {};
-                prefill_step<NB, false>(ks_lane, vs_lane, b, lim, qf, oacc, m, lsum, scale_log2e,
-                                        raise_margin);
-            }
+            for (int nb = 0; nb < NB; ++nb) lim[nb] = min(n_valid, i_row[nb] - kpos + 1);
+            prefill_step(ks_lane, vs_lane, b, lim, qf, oacc, m, lsum, scale_log2e, raise_margin);
         }
 
         __syncthreads();  // the staged tile has been read by every wave

@@ -40,11 +40,11 @@ def test_prefill_plan_fuzz_matches_oracle_walk(seed):
     hkv, hq = [(2, 8), (1, 1), (2, 16), (4, 8)][seed % 4]
     with _ctx(hkv, hq) as ctx:
         st = _check(ctx, t)
-        # a block holds 128 / G query tokens
+        # a block holds rows_per_item / G query tokens
         G = hq // hkv
         lens = t.n_tokens[t.leaf_node]
-        assert st.n_items == int(sum(-(-int(n) // (128 // G)) for n in lens))
-        assert st.rows_per_item == 128
+        assert st.rows_per_item % 64 == 0
+        assert st.n_items == int(sum(-(-int(n) // (st.rows_per_item // G)) for n in lens))
 
 
 @pytest.mark.parametrize("name", ["c2_w16", "c3_pruned", "c4_34b"])
@@ -61,12 +61,13 @@ def test_prefill_plan_on_configs(name):
 
 def test_prefill_closed_form_counts():
     # root of 40 rows, two children of 70 and 5 rows, leaf queries on both children and
-    # on the root itself; G = 4 => 32 query tokens per item
+    # on the root itself
     t = Tree(np.array([-1, 0, 0], np.int32), np.array([0, 40, 110], np.int64),
              np.array([40, 70, 5], np.int32), np.array([1, 2, 0], np.int32), 115)
     with _ctx(2, 8) as ctx:
         st = _check(ctx, t)
-        assert st.n_q_rows == 115 and st.n_items == 3 + 1 + 2
+        tq = st.rows_per_item // 4
+        assert st.n_q_rows == 115 and st.n_items == -(-70 // tq) + 1 + -(-40 // tq)
         # pairs: child 1: 70 * 40 + 70 * 71 / 2; child 2: 5 * 40 + 15; root: 40 * 41 / 2
         assert st.visible_pairs == 70 * 40 + 70 * 71 // 2 + 5 * 40 + 15 + 40 * 41 // 2
         assert st.unique_tokens == 115 and st.min_pool_tokens == 115
