@@ -585,7 +585,7 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
     // grid: x = kv head, y = item, at most 65535 items per launch
     for (int64_t y0 = 0; y0 < st.n_items; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, st.n_items - y0);
-        hipLaunchKernelGGL(prefill_attn_kernel, dim3((unsigned)ctx->shape.n_kv_heads, ny), dim3(256),
+        hipLaunchKernelGGL(prefill_attn_kernel, dim3((unsigned)ctx->shape.n_kv_heads, ny), dim3(512),
                            0, stream, static_cast<const bf16_t*>(k_pool),
                            static_cast<const bf16_t*>(v_pool), pool_tokens,
                            static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items, (int)y0,

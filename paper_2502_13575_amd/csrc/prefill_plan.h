@@ -16,7 +16,7 @@ namespace ets {
 // run's first row; rows of ancestors carry kAncestorRun and are seen by every query.
 // Query token i sees row t of a run iff t < n and kpos + t <= i.
 constexpr int32_t kAncestorRun = -(1 << 30);
-constexpr int32_t kPrefillRowsPerItem = 128;  // query rows (tokens x heads per kv head)
+constexpr int32_t kPrefillRowsPerItem = 256;  // query rows (tokens x heads per kv head)
 
 // Work item of the prefill kernel: query tokens [tok0, tok0 + n_tok) of one leaf
 // query's node against runs [run_begin, run_end): the ancestors' rows, then the node's
