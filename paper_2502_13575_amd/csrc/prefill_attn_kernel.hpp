@@ -34,6 +34,7 @@
 // The work on a run is software pipelined inside the wave, because matrix and vector
 // instructions only overlap when they alternate in program order:
 //   [ scores(u + 1) || weights(u) ]  [ apply(u) || mask, maximum(u + 1) ]  raise(u + 1)
+// (half t of the weights takes the scores of c = 2 t and 2 t + 1)
 // and the pipeline runs on across tiles: the first run of the next tile is read from
 // the next LDS buffer.  Three tile buffers rotate, so that the next tile can be staged
 // while the previous one may still be read by a slower wave: one barrier per tile (new
@@ -52,21 +53,6 @@
 namespace ets {
 
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-// Issue order of the surrounding basic block: n groups of one matrix instruction, one LDS
-// read (a fragment for a matrix instruction several groups on: LDS latency is longer than
-// a group) and `valu` vector-ALU instructions.
-template <int N, int VALU>
-__device__ __forceinline__ void interleave_mfma_valu() {
-    constexpr int AHEAD = 4;  // fragments in flight before the first matrix instruction
-    __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-        if (i + AHEAD < N) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-        __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);  // VALU
-    }
-}
 
 // Scores of the wave's 32 query rows against one staged run: S^T = K Q^T.
 // ks_lane: the run's K rows in LDS at row n, 16-byte unit g.
@@ -107,21 +93,6 @@ __device__ __forceinline__ void prefill_raise(float mx, float& m, float& lsum, f
     }
 }
 
-// Weights of the masked scores against the reference, rounded to fp16 for the P V
-// product: half t takes the scores of c = 2 t and 2 t + 1.
-__device__ __forceinline__ void prefill_weights(const f32x16_t& s, float m, float& lsum,
-                                                float scale_log2e, f16x8_t (&pf)[2]) {
-    const float mc = m * scale_log2e;
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float p = fast_exp2(fmaf(s[i], scale_log2e, -mc));
-        psum += p;
-        pf[i >> 3][i & 7] = (_Float16)p;
-    }
-    lsum += psum;
-}
-
 // Where lane s of a V^T fragment of d block x sits inside the fragment's 64 slots of 16
 // bytes.  The staging writes of one instruction go to 8 slots in each of the 4 d blocks;
 // the swizzle spreads those 32 slots evenly over the LDS banks (two per bank group, the
@@ -131,17 +102,67 @@ __device__ __forceinline__ int vfrag_slot(int s, int x) {
     return (s & 48) | ((s & 15) ^ k);
 }
 
-// O^T += V^T P^T for one staged run.  vs_run: the run's V^T fragments [half t][d block]
-// [slot] in LDS; slot_x[x]: the lane's slot in a fragment of d block x.
-__device__ __forceinline__ void prefill_apply(const u32x4_t* __restrict__ vs_run, const int (&slot_x)[4],
-                                              const f16x8_t (&pf)[2], f32x16_t (&oacc)[4]) {
+// One pipeline stage: the scores of run u + 1 and the weights of run u, then the
+// application of run u's weights and the masking of run u + 1's scores, written in the
+// order in which it is to be issued: every matrix instruction is followed by the LDS read
+// of a fragment four instructions on and by two scores' worth of vector arithmetic, and a
+// scheduling fence keeps the group together.  Matrix and vector instructions of one wave
+// overlap only when they alternate like this.
+//   ks_next  K rows of run u + 1 in LDS (at row n, 16-byte unit g)
+//   vs_run   V^T fragments of run u
+//   s_cur    masked scores of run u (in), s_next: masked scores of run u + 1 (out)
+// Returns the lane's largest score of run u + 1.
+__device__ __forceinline__ float prefill_unit(const u32x4_t* __restrict__ ks_next,
+                                              const u32x4_t* __restrict__ vs_run,
+                                              const int (&slot_x)[4], const bf16x8_t (&qf)[8],
+                                              const f32x16_t& s_cur, f32x16_t& s_next, int g,
+                                              int lim_next, float m, float& lsum, f32x16_t (&oacc)[4],
+                                              float scale_log2e) {
+    constexpr int AHEAD = 4;
+    u32x4_t fr[AHEAD];
+    f16x8_t pf[2];
+    const float mc = m * scale_log2e;
+    float psum = 0.f;
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(vs_run[x * 64 + slot_x[x]]), pf[0],
-                                                         oacc[x], 0, 0, 0);
-        oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(vs_run[(4 + x) * 64 + slot_x[x]]), pf[1],
-                                                         oacc[x], 0, 0, 0);
+    for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < AHEAD; ++kk) fr[kk] = ks_next[2 * kk];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[kk % AHEAD]), qf[kk], s_next, 0, 0, 0);
+        if (kk + AHEAD < 8) fr[kk % AHEAD] = ks_next[2 * (kk + AHEAD)];
+        const float p0 = fast_exp2(fmaf(s_cur[2 * kk], scale_log2e, -mc));
+        const float p1 = fast_exp2(fmaf(s_cur[2 * kk + 1], scale_log2e, -mc));
+        psum += p0 + p1;
+        pf[kk >> 2][2 * (kk & 3)] = (_Float16)p0;
+        pf[kk >> 2][2 * (kk & 3) + 1] = (_Float16)p1;
+        __builtin_amdgcn_sched_barrier(0);
     }
+    lsum += psum;
+    // apply(u): d block x, half t, both halves of a block back to back
+#pragma unroll
+    for (int j = 0; j < AHEAD; ++j) fr[j] = vs_run[((j & 1) * 4 + (j >> 1)) * 64 + slot_x[j >> 1]];
+    __builtin_amdgcn_sched_barrier(0);
+    const int rem = lim_next - 4 * g;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int x = j >> 1, t = j & 1;
+        oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fr[j % AHEAD]), pf[t], oacc[x], 0, 0, 0);
+        if (j + AHEAD < 8) {
+            const int jn = j + AHEAD;
+            fr[j % AHEAD] = vs_run[((jn & 1) * 4 + (jn >> 1)) * 64 + slot_x[jn >> 1]];
+        }
+        // scores 2 j and 2 j + 1 of run u + 1 stand for run rows 8 (i / 4) + 4 g + i % 4
+#pragma unroll
+        for (int i = 2 * j; i < 2 * j + 2; ++i) {
+            s_next[i] = (8 * (i >> 2) + (i & 3)) < rem ? s_next[i] : -INFINITY;
+            mx = fmaxf(mx, s_next[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return mx;
 }
 
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attn_kernel(
@@ -291,7 +312,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 #pragma unroll
     for (int x = 0; x < 4; ++x) slot_x[x] = vfrag_slot(lane, x);
     f32x16_t s_a, s_b;  // scores of the runs in flight (even and odd run of a tile)
-    f16x8_t pf[2];
     {
         // first run: scores, mask and maximum
         prefill_scores(smem + n * KROW + g, qf, s_a);
@@ -321,23 +341,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
             sm_desc[refill_idx & (RING - 1)] = desc_raw;
 
         // [ scores(run 1) || weights(run 0) ]  [ apply(run 0) || mask, maximum(run 1) ]
-        prefill_scores(ks + (32 + n) * KROW + g, qf, s_b);
-        prefill_weights(s_a, m, lsum, scale_log2e, pf);
-        interleave_mfma_valu<8, 7>();
-        prefill_apply(vs, slot_x, pf, oacc);
-        const float mx1 = prefill_mask_max(s_b, g, lim_of(d1));
-        interleave_mfma_valu<8, 6>();
+        const float mx1 = prefill_unit(ks + (32 + n) * KROW + g, vs, slot_x, qf, s_a, s_b, g, lim_of(d1),
+                                       m, lsum, oacc, scale_log2e);
         prefill_raise(mx1, m, lsum, oacc, scale_log2e, raise_margin);
 
         __syncthreads();  // the next tile is staged
         // [ scores(next tile, run 0) || weights(run 1) ]  [ apply(run 1) || mask, maximum ]
         // (past the last tile the scores are masked away as a whole)
-        prefill_scores(ks_next + n * KROW + g, qf, s_a);
-        prefill_weights(s_b, m, lsum, scale_log2e, pf);
-        interleave_mfma_valu<8, 7>();
-        prefill_apply(vs + 8 * 64, slot_x, pf, oacc);
-        const float mx0 = prefill_mask_max(s_a, g, lim_of(d2));
-        interleave_mfma_valu<8, 6>();
+        const float mx0 = prefill_unit(ks_next + n * KROW + g, vs + 8 * 64, slot_x, qf, s_b, s_a, g,
+                                       lim_of(d2), m, lsum, oacc, scale_log2e);
         prefill_raise(mx0, m, lsum, oacc, scale_log2e, raise_margin);
         cur = nxt;
         nxt = nxt == 2 ? 0 : nxt + 1;
