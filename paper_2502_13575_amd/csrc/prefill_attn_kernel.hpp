@@ -39,7 +39,8 @@
 // the next LDS buffer.  Three tile buffers rotate, so that the next tile can be staged
 // while the previous one may still be read by a slower wave: one barrier per tile (new
 // contents visible), and the staging sits in the same basic block as the matrix work.
-// K and V are fetched with range-checked buffer loads, two tiles ahead of their use:
+// K and V are fetched with range-checked buffer loads, three tiles ahead of their use
+// (two register sets alternate; one tile ahead left the waves waiting for memory):
 // waves 0..3 each fetch and stage half a run (16 rows, 16 bytes per lane and load) of K,
 // waves 4..7 of V.  The run list can be long (a
 // path of thousands of rows), so its descriptors travel through a ring of 256 entries in
@@ -198,7 +199,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     const Run* my_runs = runs + it.run_begin;
     const float raise_margin = 8.0f / scale_log2e;
 
-    u32x4_t raw[4];  // the wave's 16 rows of K (rows b + 4 i) or of V (rows 4 b + i)
+    // the wave's 16 rows of K (rows b + 4 i) or of V (rows 4 b + i) of two tiles in flight:
+    // loads are issued three tiles ahead of their use, and a register set is busy from
+    // the issue until its tile is staged, so two sets alternate
+    u32x4_t raw0[4], raw1[4];
     constexpr uint32_t stride_b = D * 2;
     const int64_t plane = (int64_t)h * pool_tokens;
     const bf16_t* pool = loads_v ? v_pool : k_pool;
@@ -207,25 +211,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     // a run's rows through a descriptor that covers exactly the run: rows past the end of
     // a short run read as zero (and are masked); an empty run (past the end of an odd
     // list) is staged as zeros
-    auto issue_loads = [&](const Run& sd) {
-        if (sd.n > 0) {
-            const int64_t base = (plane + sd.tok) * (int64_t)D * 2;
-            char* pb = const_cast<char*>(reinterpret_cast<const char*>(pool)) + base;
-            const int bytes = sd.n * (int)stride_b;
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(pb, 0, bytes, 0x00020000);
+    auto issue_loads = [&](const Run& sd, u32x4_t (&raw)[4]) {
+        // always four loads (an empty run's descriptor covers nothing: every lane reads
+        // zero without a memory access), so that the number of loads in flight is known
+        // at every wait
+        const int64_t base = (plane + sd.tok) * (int64_t)D * 2;
+        char* pb = const_cast<char*>(reinterpret_cast<const char*>(pool)) + base;
+        const int bytes = sd.n * (int)stride_b;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(pb, 0, bytes, 0x00020000);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                raw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                         rs, lane_off + (uint32_t)i * load_step, 0, 0));
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) raw[i] = u32x4_t{0u, 0u, 0u, 0u};
-        }
+        for (int i = 0; i < 4; ++i)
+            raw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                     rs, lane_off + (uint32_t)i * load_step, 0, 0));
     };
     // K: row-major rows of 272 bytes.  V: lane (a, b) holds run rows 16 hw + 4 b + i
     // (i = 0..3) at d = 8 a + x (x = 0..7); the four rows at one d are half (b >> 1) of
     // the 16-byte A fragment of lane (d % 32, b & 1) in d block d / 32 of half hw.
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, const u32x4_t (&raw)[4]) {
         u32x4_t* ks = smem + buf * BUF_UNITS;
         u32x2_t* vs2 = reinterpret_cast<u32x2_t*>(ks + KS_UNITS);
         if (!loads_v) {
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     };
 
     // prologue: first tile, the first 256 descriptors, the query rows
-    issue_loads(sw < n_runs ? my_runs[sw] : Run{0, 0, 0});
+    issue_loads(sw < n_runs ? my_runs[sw] : Run{0, 0, 0}, raw0);
     u32x4_t desc_raw = {0u, 0u, 0u, 0u};
     if ((int)threadIdx.x < min(n_runs, RING))
         desc_raw = load16(reinterpret_cast<const char*>(my_runs + threadIdx.x));
@@ -293,10 +295,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     for (int x = 0; x < 4; ++x)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[x][i] = 0.f;
-    stage(0);
-    // the second tile's loads are in flight while the first is computed (its descriptors
-    // straight from memory: the ring is not visible before the barrier)
-    issue_loads(2 + sw < n_runs ? my_runs[2 + sw] : Run{0, 0, 0});
+    stage(0, raw0);
+    // the loads of the second and third tile are in flight while the first is computed
+    // (their descriptors straight from memory: the ring is not visible before the barrier)
+    issue_loads(2 + sw < n_runs ? my_runs[2 + sw] : Run{0, 0, 0}, raw0);
+    issue_loads(4 + sw < n_runs ? my_runs[4 + sw] : Run{0, 0, 0}, raw1);
     __syncthreads();  // descriptors and the first tile are in LDS
 
     auto lim_of = [&](const u32x4_t& d) {
@@ -320,7 +323,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     }
 
     int cur = 0, nxt = 1;  // tile % 3, (tile + 1) % 3
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    // one tile; `raw` holds the rows of tile + 1 and takes those of tile + 3
+    auto do_tile = [&](int tile, u32x4_t (&raw)[4]) {
         const u32x4_t* ks = smem + cur * BUF_UNITS;
         const u32x4_t* vs = ks + KS_UNITS;
         const u32x4_t* ks_next = smem + nxt * BUF_UNITS;
@@ -335,8 +339,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 
         // the buffer of tile - 2 is free: every wave has passed the barrier of tile - 1.
         // Past the end of the list zeros are staged (never read).
-        stage(nxt);  // waits for the loads of tile + 1
-        issue_loads(read_desc(2 * (tile + 2) + sw));
+        stage(nxt, raw);  // waits for the loads of tile + 1
+        issue_loads(read_desc(2 * (tile + 3) + sw), raw);
         if (refill && threadIdx.x < 128 && refill_idx < n_runs)
             sm_desc[refill_idx & (RING - 1)] = desc_raw;
 
@@ -353,7 +357,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
         prefill_raise(mx0, m, lsum, oacc, scale_log2e, raise_margin);
         cur = nxt;
         nxt = nxt == 2 ? 0 : nxt + 1;
+    };
+    // (no branch inside the loop body: the waits for a register set then leave the other
+    // set's loads in flight)
+    for (int tile = 0; tile + 1 < n_tiles; tile += 2) {
+        do_tile(tile, raw0);
+        do_tile(tile + 1, raw1);
     }
+    if (n_tiles & 1) do_tile(n_tiles - 1, raw0);
     __syncthreads();  // every wave is done with the tiles: the epilogue reuses the buffers
 
     // normalised rows out through the wave's own LDS region (16 rows padded to 132 floats,
