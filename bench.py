@@ -21,41 +21,44 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 / fp16 matrix-core peak, published
 
 
-def measured_traffic(workload):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
-    counter summary, or None when the kernel or planner changed since it was taken."""
+# sources whose change invalidates a stored counter reading, per kernel
+TRAFFIC_SOURCES = {"tree_attn": ("tree_attn_kernel.hpp", "plan.cpp"),
+                   "prefill_attn": ("prefill_attn_kernel.hpp", "prefill_plan.cpp")}
+
+
+def _traffic_file(kernel, workload):
     import hashlib
     import os
     root = os.path.dirname(os.path.abspath(__file__))
-    path = os.path.join(root, "profiles", "traffic_tree_attn_%s.json" % workload)
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES[kernel]:
+        h.update(open(os.path.join(root, "paper_2502_13575_amd", "csrc", f), "rb").read())
+    return (os.path.join(root, "profiles", "traffic_%s_%s.json" % (kernel, workload)),
+            h.hexdigest()[:16])
+
+
+def measured_traffic(workload, kernel="tree_attn"):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary, or
+    None when the kernel or its planner changed since the counters were taken."""
     try:
+        path, digest = _traffic_file(kernel, workload)
         rec = json.load(open(path))
-        h = hashlib.sha256()
-        for f in ("tree_attn_kernel.hpp", "plan.cpp"):
-            h.update(open(os.path.join(root, "paper_2502_13575_amd", "csrc", f), "rb").read())
-        if h.hexdigest()[:16] != rec["source_sha256_16"]:
+        if digest != rec["source_sha256_16"]:
             return None
         return int(rec["hbm_bytes_per_launch"])
     except (OSError, ValueError, KeyError):
         return None
 
 
-def record_traffic(workload, fetch_kib, write_kib, fetch_scale, write_scale):
-    """Writes profiles/traffic_tree_attn_<workload>.json from `rocprofv3 --pmc FETCH_SIZE`
+def record_traffic(workload, kernel, fetch_kib, write_kib, fetch_scale, write_scale):
+    """Writes profiles/traffic_<kernel>_<workload>.json from `rocprofv3 --pmc FETCH_SIZE`
     and `--pmc WRITE_SIZE` readings (KiB per launch) of this script, scaled by what the
     same counters read for the plain 1 GiB copy of --calibrate-copy."""
-    import hashlib
-    import os
-    root = os.path.dirname(os.path.abspath(__file__))
-    h = hashlib.sha256()
-    for f in ("tree_attn_kernel.hpp", "plan.cpp"):
-        h.update(open(os.path.join(root, "paper_2502_13575_amd", "csrc", f), "rb").read())
-    rec = {"kernel": "tree_attn_kernel", "workload": workload,
-           "source_sha256_16": h.hexdigest()[:16],
+    path, digest = _traffic_file(kernel, workload)
+    rec = {"kernel": kernel + "_kernel", "workload": workload, "source_sha256_16": digest,
            "fetch_size_kib_per_launch": fetch_kib, "fetch_scale": fetch_scale,
            "write_size_kib_per_launch": write_kib, "write_scale": write_scale,
            "hbm_bytes_per_launch": int(round((fetch_kib * fetch_scale + write_kib * write_scale) * 1024))}
-    path = os.path.join(root, "profiles", "traffic_tree_attn_%s.json" % workload)
     with open(path, "w") as f:
         json.dump(rec, f, indent=1)
     print(path, rec)
@@ -86,10 +89,12 @@ def main():
                     help="no GPU work: store FETCH_SIZE and WRITE_SIZE readings (KiB per launch, "
                          "then optionally their scales, default 2.0 and 1.0) for the roofline's "
                          "traffic field")
+    ap.add_argument("--traffic-kernel", default="tree_attn", choices=sorted(TRAFFIC_SOURCES),
+                    help="the kernel that --record-traffic is about")
     args = ap.parse_args()
     if args.record_traffic:
         v = args.record_traffic + [2.0, 1.0][max(0, len(args.record_traffic) - 2):]
-        record_traffic(args.config, v[0], v[1], v[2], v[3])
+        record_traffic(args.config, args.traffic_kernel, v[0], v[1], v[2], v[3])
         return
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -305,7 +310,8 @@ def main():
                    "roofline": {"bound": "mfma", "kernel": "prefill_attn_kernel",
                                 "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS,
                                 "unit": "TFLOP/s", "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
-                                "traffic": None, "avg_launch_us": round(ms_l * 1e3, 1)}}
+                                "traffic": measured_traffic(cfg.name, "prefill_attn"),
+                                "avg_launch_us": round(ms_l * 1e3, 1)}}
         log("step prefill: %d query tokens, %.1f TFLOP per layer, %.2f ms per layer = "
             "%.0f TFLOP/s (%.1f%% of the %d TFLOP/s matrix-core peak)" %
             (nq, pst.flops / 1e12, ms_l, tflops, tflops / MFMA_PEAK_TFLOPS * 100,
