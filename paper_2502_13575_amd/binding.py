@@ -71,6 +71,12 @@ def load_library():
         raise ImportError(
             "libetsattn.so is not built: run `python -m paper_2502_13575_amd.build` "
             "(there is no CPU fallback for the attention path)")
+    try:
+        # device buffers come from PyTorch: load it first, so that this library binds to
+        # the HIP runtime torch brings along instead of loading a second one
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(_LIB_PATH)
     vp = C.c_void_p
     i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
