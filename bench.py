@@ -82,6 +82,9 @@ def main():
                     help="decode tokens of the append/advance measurement on one extra pool (0 = skip)")
     ap.add_argument("--prefill-layers", type=int, default=4,
                     help="timed layers of step-prefill attention on the same tree (0 = skip)")
+    ap.add_argument("--select", type=int, default=1,
+                    help="1 = also run the ETS selection step on the tree's leaves and time "
+                         "decode attention on the pruned tree (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "scaling hardware byte counters when profiling)")
@@ -320,6 +323,53 @@ def main():
             del qp
         del outp, lsep
 
+    selector = None
+    if args.select:
+        # The ETS selection step on this tree's leaves (synthetic rewards and cluster labels
+        # stand in for the PRM and the sentence embeddings), then decode attention on what
+        # is kept: lambda_b trades retained weight against retained nodes (paper Sec. 4.1).
+        rs = np.random.default_rng(cfg.seed + 5)
+        rewards = rs.random(L)
+        clusters = rs.integers(0, max(1, L // 8), size=L)
+        t0 = time.perf_counter()
+        w_sel = ets.ets_rebase_weights(rewards, L, 0.2)
+        rebase_ms = (time.perf_counter() - t0) * 1e3
+        selector = {"rebase_temperature": 0.2, "lambda_d": 1.0, "clusters": int(len(set(clusters))),
+                    "rebase_ms": round(rebase_ms, 3), "runs": []}
+        for lam_b in (1.0, 1.5, 2.0):
+            t0 = time.perf_counter()
+            keep, info = ets.ets_select_leaves(tree.parent, tree.leaf_node, w_sel, clusters, lam_b,
+                                               1.0, node_limit=200000)
+            sel_ms = (time.perf_counter() - t0) * 1e3
+            kept = np.flatnonzero(keep)
+            stp = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node[kept],
+                           ets.ETS_PLAN_TREE)
+            ws = torch.empty(max(stp.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+            nk = len(kept)
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            for rep in range(2):
+                if rep == 1:
+                    evs[0].record(stream)
+                for p_ in range(min(8, n_pools)):
+                    k_, v_, q_, o_, l_ = pools[p_]
+                    ctx.decode(k_, v_, tree.pool_tokens, q_[:nk], o_[:nk], l_[:nk], ws, ws.numel(),
+                               stream.cuda_stream)
+            evs[1].record(stream)
+            torch.cuda.synchronize()
+            us = evs[0].elapsed_time(evs[1]) / min(8, n_pools) * 1e3
+            selector["runs"].append({
+                "lambda_b": lam_b, "select_ms": round(sel_ms, 3), "optimal": int(info.optimal),
+                "bb_nodes": int(info.bb_nodes), "objective": round(info.objective, 6),
+                "kept_leaves": int(nk), "kept_nodes": int(info.kept_nodes),
+                "live_nodes": int(info.live_nodes), "kept_clusters": int(info.kept_clusters),
+                "kept_unique_kv_bytes": int(stp.unique_kv_bytes),
+                "decode_us_per_layer": round(us, 1)})
+            log("select lambda_b %.1f: %.2f ms (%d nodes, optimal %d), keeps %d of %d leaves, "
+                "%d of %d nodes, %d of %d clusters; decode %.0f us per layer (full tree %.0f)" %
+                (lam_b, sel_ms, info.bb_nodes, info.optimal, nk, L, info.kept_nodes,
+                 info.live_nodes, info.kept_clusters, info.clusters, us,
+                 kernel_us["tree_attn"] + kernel_us["merge"]))
+
     cpu = None
     parity = None
     if args.cpu_seconds > 0:
@@ -414,6 +464,7 @@ def main():
         "flat_baseline": flat,
         "decode_step": decode_step,
         "prefill": prefill,
+        "selector": selector,
         "parity_sample": parity,
         "paper_context": "ETS reports 1.8x smaller KV and 1.4x search throughput vs REBASE on "
                          "2x H100 NVL with stock kernels; no kernel-level numbers",

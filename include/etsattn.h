@@ -296,6 +296,46 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
                                  int64_t pool_tokens, const void* q, float* out, float* lse,
                                  void* hip_stream);
 
+/* ---- The selection step that produces the tree (host only, no context) ---------------
+ *
+ * ETS decides at every search step which trajectories to keep (ETS paper Sec. 4.1-4.2;
+ * App. A).  ets_rebase_weights is Eq. 1 (and Eq. 3 when called on the kept set): the
+ * trajectories are visited from the highest reward to the lowest, equal rewards in input
+ * order; trajectory i receives W_i = ceil(N_i e_i / sum_{k in A_i} e_k) continuations,
+ * e = exp(R / temperature), A_i = i and everything after it, N_1 = budget and
+ * N_{i+1} = N_i - W_i (the recurrence the paper implies); fp64.
+ *   rewards  HOST [n];  weights  HOST [n], written;  budget >= 0, temperature > 0.
+ *
+ * ets_select_leaves maximises the cost model of Eq. 5 / Eq. 7 exactly:
+ *     sum_{i kept} W_i / sum_i W_i  -  lambda_b |V_S| / |V_A|  +  lambda_d |C_S| / |C_A|
+ * V_A = the nodes with a leaf at or beneath them, V_S = those with a KEPT leaf at or
+ * beneath them, C_A / C_S = the clusters present / with a kept leaf (the text's reading
+ * of the cluster constraint: a cluster counts when ANY of its leaves is kept), at least
+ * one leaf kept.
+ *   tree      only parent and leaf_node are read; the leaves must be distinct nodes and
+ *             none may lie beneath another (ETS_ERR_BAD_LEAF)
+ *   weights   HOST [n_leaves], >= 0, not all zero
+ *   cluster   HOST [n_leaves] arbitrary ids, or NULL for no coverage term
+ *   node_limit  branch-and-bound nodes to spend (<= 0: 2^22); when it is reached the best
+ *             set found so far is returned with info->optimal = 0
+ *   keep      HOST [n_leaves], written: 1 = kept
+ *   info      HOST, may be NULL */
+typedef struct {
+    double objective;
+    int64_t kept_nodes;    /* |V_S| */
+    int64_t live_nodes;    /* |V_A| */
+    int64_t kept_clusters; /* |C_S| */
+    int64_t clusters;      /* |C_A|, 0 without coverage term */
+    int64_t bb_nodes;      /* branch-and-bound nodes visited */
+    int32_t optimal;
+    int32_t pad;
+} ets_select_info;
+ets_status ets_rebase_weights(int32_t n, const double* rewards, int32_t budget,
+                              double temperature, int32_t* weights);
+ets_status ets_select_leaves(const ets_tree* tree, const int32_t* weights, const int32_t* cluster,
+                             double lambda_b, double lambda_d, int64_t node_limit, uint8_t* keep,
+                             ets_select_info* info);
+
 /* Static string for a status code. */
 const char* ets_strerror(int status);
 

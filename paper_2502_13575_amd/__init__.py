@@ -8,7 +8,7 @@ from .binding import (ETS_BF16, ETS_F32, ETS_PLAN_FLAT, ETS_PLAN_TREE, Context, 
                       ets_plan_leaf_cover, ets_plan_paths, ets_plan_stats, ets_profile_read, ets_set_option,
                       ets_kv_append, ets_plan_advance, EtsPrefillStats, ets_plan_prefill,
                       ets_prefill_plan_stats, ets_prefill_q_ptr, ets_prefill_cover,
-                      ets_tree_prefill_attn,
+                      ets_tree_prefill_attn, EtsSelectInfo, ets_rebase_weights, ets_select_leaves,
                       ets_strerror, ets_tree_decode_attn, library_path, load_library)
 
 __all__ = [
@@ -17,5 +17,6 @@ __all__ = [
     "ets_plan_leaf_cover", "ets_plan_paths", "ets_plan_stats", "ets_set_option", "ets_strerror",
     "ets_kv_append", "ets_plan_advance", "EtsPrefillStats", "ets_plan_prefill",
     "ets_prefill_plan_stats", "ets_prefill_q_ptr", "ets_prefill_cover", "ets_tree_prefill_attn",
+    "EtsSelectInfo", "ets_rebase_weights", "ets_select_leaves",
     "ets_tree_decode_attn", "library_path", "load_library",
 ]

@@ -53,6 +53,12 @@ class EtsPrefillStats(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+class EtsSelectInfo(C.Structure):
+    _fields_ = [("objective", C.c_double), ("kept_nodes", C.c_int64), ("live_nodes", C.c_int64),
+                ("kept_clusters", C.c_int64), ("clusters", C.c_int64), ("bb_nodes", C.c_int64),
+                ("optimal", C.c_int32), ("pad", C.c_int32)]
+
+
 class EtsProfile(C.Structure):
     _fields_ = [("calls", C.c_int64), ("stream_ms", C.c_double), ("cascade_ms", C.c_double),
                 ("merge_ms", C.c_double)]
@@ -112,6 +118,11 @@ def load_library():
     lib.ets_prefill_cover.argtypes = [vp, C.c_int32, C.c_int32, i64p, C.c_int64, i64p]
     lib.ets_tree_prefill_attn.restype = C.c_int
     lib.ets_tree_prefill_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp]
+    lib.ets_rebase_weights.restype = C.c_int
+    lib.ets_rebase_weights.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_int32, C.c_double, i32p]
+    lib.ets_select_leaves.restype = C.c_int
+    lib.ets_select_leaves.argtypes = [C.POINTER(_EtsTree), i32p, i32p, C.c_double, C.c_double,
+                                      C.c_int64, C.POINTER(C.c_uint8), C.POINTER(EtsSelectInfo)]
     lib.ets_profile_read.restype = C.c_int
     lib.ets_profile_read.argtypes = [vp, C.POINTER(EtsProfile)]
     lib.ets_strerror.restype = C.c_char_p
@@ -281,6 +292,42 @@ def ets_plan_advance(ctx, stream=None) -> bool:
     st = None if stream is None else C.c_void_p(int(stream))
     _check(load_library().ets_plan_advance(ctx, st, C.byref(flag)), "ets_plan_advance")
     return bool(flag.value)
+
+
+def ets_rebase_weights(rewards, budget: int, temperature: float):
+    """int32 [n]: continuations per trajectory (ETS paper Eq. 1)."""
+    r = np.ascontiguousarray(rewards, dtype=np.float64)
+    w = np.zeros(max(r.shape[0], 1), dtype=np.int32)
+    _check(load_library().ets_rebase_weights(r.shape[0], r.ctypes.data_as(C.POINTER(C.c_double)),
+                                             int(budget), float(temperature),
+                                             w.ctypes.data_as(C.POINTER(C.c_int32))),
+           "ets_rebase_weights")
+    return w[:r.shape[0]].copy()
+
+
+def ets_select_leaves(parent, leaf_node, weights, cluster=None, lambda_b=1.0, lambda_d=0.0,
+                      node_limit=0):
+    """(keep bool [L], EtsSelectInfo): the kept leaves that maximise the cost model."""
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    leaf_node = np.ascontiguousarray(leaf_node, dtype=np.int32)
+    weights = np.ascontiguousarray(weights, dtype=np.int32)
+    if weights.shape != leaf_node.shape:
+        raise ValueError("one weight per leaf")
+    t = _EtsTree(parent.shape[0], parent.ctypes.data_as(C.POINTER(C.c_int32)), None, None,
+                 leaf_node.shape[0], leaf_node.ctypes.data_as(C.POINTER(C.c_int32)))
+    cl = None
+    if cluster is not None:
+        cl = np.ascontiguousarray(cluster, dtype=np.int32)
+        if cl.shape != leaf_node.shape:
+            raise ValueError("one cluster id per leaf")
+    keep = np.zeros(max(leaf_node.shape[0], 1), dtype=np.uint8)
+    info = EtsSelectInfo()
+    _check(load_library().ets_select_leaves(
+        C.byref(t), weights.ctypes.data_as(C.POINTER(C.c_int32)),
+        None if cl is None else cl.ctypes.data_as(C.POINTER(C.c_int32)), float(lambda_b),
+        float(lambda_d), int(node_limit), keep.ctypes.data_as(C.POINTER(C.c_uint8)),
+        C.byref(info)), "ets_select_leaves")
+    return keep[:leaf_node.shape[0]].astype(bool), info
 
 
 def ets_profile_read(ctx) -> EtsProfile:

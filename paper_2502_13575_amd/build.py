@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libetsattn.so")
-SOURCES = ["plan.cpp", "prefill_plan.cpp", "etsattn.hip"]
+SOURCES = ["plan.cpp", "prefill_plan.cpp", "selector.cpp", "etsattn.hip"]
 
 
 def build(verbose: bool = False) -> str:

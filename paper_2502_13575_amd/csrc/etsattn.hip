@@ -13,6 +13,7 @@
 #include "plan.h"
 #include "prefill_attn_kernel.hpp"
 #include "prefill_plan.h"
+#include "selector.h"
 #include "stream_kernel.hpp"
 #include "tree_attn_kernel.hpp"
 
@@ -594,6 +595,39 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
     ctx->last_stream = stream;
     ctx->stream_used = true;
     if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    return ETS_OK;
+}
+
+ets_status ets_rebase_weights(int32_t n, const double* rewards, int32_t budget,
+                              double temperature, int32_t* weights) {
+    if (n < 0 || budget < 0 || !(temperature > 0.0)) return ETS_ERR_INVALID_ARG;
+    if (n > 0 && (!rewards || !weights)) return ETS_ERR_INVALID_ARG;
+    try {
+        rebase_weights(n, rewards, budget, temperature, weights);
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+    return ETS_OK;
+}
+
+ets_status ets_select_leaves(const ets_tree* tree, const int32_t* weights, const int32_t* cluster,
+                             double lambda_b, double lambda_d, int64_t node_limit, uint8_t* keep,
+                             ets_select_info* info) {
+    if (!tree || !keep) return ETS_ERR_INVALID_ARG;
+    SelectResult r;
+    const ets_status s = select_leaves(*tree, weights, cluster, lambda_b, lambda_d, node_limit, r);
+    if (s != ETS_OK) return s;
+    std::memcpy(keep, r.keep.data(), r.keep.size());
+    if (info) {
+        info->objective = r.objective;
+        info->kept_nodes = r.kept_nodes;
+        info->live_nodes = r.live_nodes;
+        info->kept_clusters = r.kept_clusters;
+        info->clusters = r.clusters;
+        info->bb_nodes = r.bb_nodes;
+        info->optimal = r.optimal ? 1 : 0;
+        info->pad = 0;
+    }
     return ETS_OK;
 }
 
