@@ -258,3 +258,34 @@ def test_kv_append_rejects_a_pool_without_room():
         with pytest.raises(ets.EtsError) as e:
             ctx.kv_append(k, v, tree.pool_tokens, q, q)
         assert e.value.status == 1  # ETS_ERR_INVALID_ARG
+
+
+def test_decode_larger_pool_custom_scale_and_side_stream():
+    """Pools with more rows per head plane than the tree needs (pool_tokens is the plane
+    stride), explicit sm_scale, launch on a non-default stream; decode steps append into
+    the spare rows."""
+    cfg = CONFIGS["c2_w16"]
+    tree = make_tree(cfg)
+    k, v, q = make_values_host(cfg, tree)
+    pad = 19
+    kp = np.concatenate([k, np.zeros((pad,) + k.shape[1:], k.dtype)], axis=0)
+    vp = np.concatenate([v, np.full((pad,) + v.shape[1:], 0x7FC0, v.dtype)], axis=0)  # NaN rows, never read
+    scale = 0.11
+    oo, ol = oracle.tree_decode_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                     k, v, q, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, scale)
+    side = torch.cuda.Stream()
+    for opts in ({}, {"mfma": 0}):
+        with ets.Context(cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, ets.ETS_BF16, 0, scale) as ctx:
+            for key, val in opts.items():
+                ctx.set_option(key, val)
+            kd, vd, qd = pool_to_device(kp), pool_to_device(vp), to_device(q)
+            st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+            L = tree.n_leaves
+            out = torch.full((L, cfg.n_q_heads, 128), float("nan"), device="cuda:0")
+            lse = torch.full((L, cfg.n_q_heads), float("nan"), device="cuda:0")
+            ws = torch.empty(max(st.workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+            torch.cuda.synchronize()
+            ctx.decode(kd, vd, tree.pool_tokens + pad, qd, out, lse, ws, ws.numel(), side.cuda_stream)
+            side.synchronize()
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "decode scale/pad/stream %s" % opts)

@@ -159,3 +159,29 @@ def test_prefill_device_error_paths():
             ctx.prefill(kd, None, tree.pool_tokens, qd, out, lse)
         assert e.value.status == 1
         assert torch.all(out == 0) and torch.all(lse == 0)
+
+
+def test_prefill_custom_scale_larger_pool_and_side_stream():
+    """sm_scale given explicitly, pools with more rows per head plane than the tree needs
+    (pool_tokens is the plane stride), launch on a non-default stream."""
+    cfg = TreeConfig("misc", 2, 8, 128, "bf16", 0, 0, 0, 0, 0, None, seed=41)
+    tree = random_tree(77, n_nodes=24, n_leaves=6, max_tokens=90, p_empty=0.1)
+    k, v, _ = make_values_host(cfg, tree)
+    q = make_prefill_queries_host(cfg, tree)
+    pad = 37
+    kp = np.concatenate([k, np.zeros((pad,) + k.shape[1:], k.dtype)], axis=0)
+    vp = np.concatenate([v, np.full((pad,) + v.shape[1:], 0x7FC0, v.dtype)], axis=0)  # NaN rows, never read
+    scale = 0.05
+    oo, ol = oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                      k, v, q, 2, 8, 128, scale)
+    side = torch.cuda.Stream()
+    with ets.Context(2, 8, 128, ets.ETS_BF16, 0, scale) as ctx:
+        kd, vd, qd = pool_to_device(kp), pool_to_device(vp), to_device(q)
+        st = ctx.plan_prefill(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        out = torch.full((st.n_q_rows, 8, 128), float("nan"), device="cuda:0")
+        lse = torch.full((st.n_q_rows, 8), float("nan"), device="cuda:0")
+        torch.cuda.synchronize()
+        ctx.prefill(kd, vd, tree.pool_tokens + pad, qd, out, lse, side.cuda_stream)
+        side.synchronize()
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1), oo.reshape(-1, 128),
+            ol.reshape(-1), "bf16", "prefill scale/pad/stream")
