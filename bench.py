@@ -370,6 +370,53 @@ def main():
                  info.live_nodes, info.kept_clusters, info.clusters, us,
                  kernel_us["tree_attn"] + kernel_us["merge"]))
 
+    search_sim = None
+    if args.select and cfg.dtype == "bf16" and d == 128:
+        # Time-summed KV size of a synthetic search (paper Sec. 3) under the two policies,
+        # and decode attention on the trees they end with (one layer, pools drawn at random).
+        from workload import simulate_search
+
+        def sel(p_, l_, w_, c_, lb_, ld_, nl_):
+            return ets.ets_select_leaves(p_, l_, w_, c_, lb_, ld_, nl_)
+
+        sw_, ss_ = 64, 12
+        res = {}
+        for pol in ("rebase", "ets"):
+            sums, us_l = [], []
+            for seed in range(3):
+                r_ = simulate_search(pol, sw_, ss_, 1024, 32, 256, 100 + seed, lambda_b=1.5,
+                                     lambda_d=1.0, select=sel, rebase=ets.ets_rebase_weights,
+                                     node_limit=5000)
+                sums.append(r_["kv_tokens_sum"])
+                t_ = r_["tree"]
+                stx = ctx.plan(t_.parent, t_.tok_offset, t_.n_tokens, t_.leaf_node, ets.ETS_PLAN_TREE)
+                tdt = torch.bfloat16
+                kx = torch.randn((cfg.n_kv_heads, t_.pool_tokens, d), device=dev).to(tdt)
+                vx = torch.randn((cfg.n_kv_heads, t_.pool_tokens, d), device=dev).to(tdt)
+                qx = torch.randn((t_.n_leaves, hq, d), device=dev).to(tdt)
+                ox = torch.empty((t_.n_leaves, hq, d), dtype=torch.float32, device=dev)
+                lx = torch.empty((t_.n_leaves, hq), dtype=torch.float32, device=dev)
+                wsx = torch.empty(max(stx.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for rep_ in range(3):
+                    if rep_ == 1:
+                        e0.record(stream)
+                    ctx.decode(kx, vx, t_.pool_tokens, qx, ox, lx, wsx, wsx.numel(), stream.cuda_stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                us_l.append(e0.elapsed_time(e1) / 2 * 1e3)
+            res[pol] = {"kv_tokens_sum_mean": float(np.mean(sums)),
+                        "last_step_decode_us_per_layer": round(float(np.mean(us_l)), 1)}
+        search_sim = {"width": sw_, "steps": ss_, "lambda_b": 1.5, "lambda_d": 1.0, "seeds": 3,
+                      "rebase": res["rebase"], "ets": res["ets"],
+                      "kv_size_ratio_rebase_over_ets": round(
+                          res["rebase"]["kv_tokens_sum_mean"] / res["ets"]["kv_tokens_sum_mean"], 3)}
+        log("synthetic search (width %d, %d steps): time-summed KV tokens rebase %.0f, ets %.0f "
+            "(ratio %.2f); decode attention on the last step %.0f vs %.0f us per layer" %
+            (sw_, ss_, res["rebase"]["kv_tokens_sum_mean"], res["ets"]["kv_tokens_sum_mean"],
+             search_sim["kv_size_ratio_rebase_over_ets"],
+             res["rebase"]["last_step_decode_us_per_layer"], res["ets"]["last_step_decode_us_per_layer"]))
+
     cpu = None
     parity = None
     if args.cpu_seconds > 0:
@@ -465,6 +512,7 @@ def main():
         "decode_step": decode_step,
         "prefill": prefill,
         "selector": selector,
+        "search_sim": search_sim,
         "parity_sample": parity,
         "paper_context": "ETS reports 1.8x smaller KV and 1.4x search throughput vs REBASE on "
                          "2x H100 NVL with stock kernels; no kernel-level numbers",

@@ -108,3 +108,32 @@ def test_selection_at_search_width_256():
     assert i1.objective == pytest.approx(
         osel.objective(t.parent, t.leaf_node, w, cluster, 1.5, 1.0, k1), abs=1e-9)
     assert i1.objective >= osel.objective(t.parent, t.leaf_node, w, cluster, 1.5, 1.0, k0) - 1e-12
+
+
+def test_simulated_search_kv_accounting():
+    """The synthetic search of workload/search_sim.py with the library's selection step:
+    deterministic, its trees are well formed (oracle's check), the per-step KV counts equal
+    the oracle's unique-token count of the final tree at the last step, and keeping the
+    cost model's set shrinks the time-summed KV size relative to continuing from every
+    weighted leaf."""
+    import oracle
+    from workload import simulate_search
+
+    def sel(p, l, w, c, lb, ld, nl):
+        return ets.ets_select_leaves(p, l, w, c, lb, ld, nl)
+
+    sums = {"rebase": [], "ets": []}
+    for seed in range(3):
+        for pol in sums:
+            r = simulate_search(pol, 32, 8, 256, 16, 64, seed, lambda_b=1.5, lambda_d=1.0,
+                                select=sel, rebase=ets.ets_rebase_weights, node_limit=5000)
+            r2 = simulate_search(pol, 32, 8, 256, 16, 64, seed, lambda_b=1.5, lambda_d=1.0,
+                                 select=sel, rebase=ets.ets_rebase_weights, node_limit=5000)
+            assert r["kv_tokens"] == r2["kv_tokens"]
+            t = r["tree"]
+            assert oracle.check_tree(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, t.pool_tokens) == 0
+            assert t.n_leaves == 32          # the width is handed out in full at every step
+            ost = oracle.tree_stats(t.parent, t.n_tokens, t.leaf_node)
+            assert ost["unique_tokens"] == r["kv_tokens"][-1]
+            sums[pol].append(r["kv_tokens_sum"])
+    assert np.mean(sums["ets"]) < np.mean(sums["rebase"])

@@ -10,8 +10,9 @@ from .trees import (CONFIGS, Tree, TreeConfig, make_tree, make_values_host,
                     make_values_device, to_bf16_bits, bf16_bits_to_f32,
                     random_tree, with_growth_room, make_new_tokens_host,
                     make_prefill_queries_host)
+from .search_sim import simulate_search
 
 __all__ = ["CONFIGS", "Tree", "TreeConfig", "make_tree", "make_values_host",
            "make_values_device", "to_bf16_bits", "bf16_bits_to_f32",
            "random_tree", "with_growth_room", "make_new_tokens_host",
-           "make_prefill_queries_host"]
+           "make_prefill_queries_host", "simulate_search"]
