@@ -281,6 +281,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     const int r_lane = 32 * w + n;
     const int tq_lane = min(r_lane >> g_shift, it.n_tok - 1);
     const int i_row = it.tok0 + tq_lane;  // the lane's query token, as an index into its node
+    // a wave whose 32 rows all lie past the block's last token (the last block of a node
+    // is rarely full) only fetches and stages: its SIMD is left to the other wave
+    const bool active = ((32 * w) >> g_shift) < it.n_tok;
     bf16x8_t qf[8];
     {
         const bf16_t* qp = q + ((it.q_row0 + tq_lane) * n_q_heads + h * G + (r_lane & (G - 1))) * D;
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 #pragma unroll
     for (int x = 0; x < 4; ++x) slot_x[x] = vfrag_slot(lane, x);
     f32x16_t s_a, s_b;  // scores of the runs in flight (even and odd run of a tile)
-    {
+    if (active) {
         // first run: scores, mask and maximum
         prefill_scores(smem + n * KROW + g, qf, s_a);
         const float mx = prefill_mask_max(s_a, g, lim_of(desc_of(0)));
@@ -345,16 +348,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
             sm_desc[refill_idx & (RING - 1)] = desc_raw;
 
         // [ scores(run 1) || weights(run 0) ]  [ apply(run 0) || mask, maximum(run 1) ]
-        const float mx1 = prefill_unit(ks + (32 + n) * KROW + g, vs, slot_x, qf, s_a, s_b, g, lim_of(d1),
-                                       m, lsum, oacc, scale_log2e);
-        prefill_raise(mx1, m, lsum, oacc, scale_log2e, raise_margin);
+        if (active) {
+            const float mx1 = prefill_unit(ks + (32 + n) * KROW + g, vs, slot_x, qf, s_a, s_b, g,
+                                           lim_of(d1), m, lsum, oacc, scale_log2e);
+            prefill_raise(mx1, m, lsum, oacc, scale_log2e, raise_margin);
+        }
 
         __syncthreads();  // the next tile is staged
         // [ scores(next tile, run 0) || weights(run 1) ]  [ apply(run 1) || mask, maximum ]
         // (past the last tile the scores are masked away as a whole)
-        const float mx0 = prefill_unit(ks_next + n * KROW + g, vs + 8 * 64, slot_x, qf, s_b, s_a, g,
-                                       lim_of(d2), m, lsum, oacc, scale_log2e);
-        prefill_raise(mx0, m, lsum, oacc, scale_log2e, raise_margin);
+        if (active) {
+            const float mx0 = prefill_unit(ks_next + n * KROW + g, vs + 8 * 64, slot_x, qf, s_b, s_a, g,
+                                           lim_of(d2), m, lsum, oacc, scale_log2e);
+            prefill_raise(mx0, m, lsum, oacc, scale_log2e, raise_margin);
+        }
         cur = nxt;
         nxt = nxt == 2 ? 0 : nxt + 1;
     };
