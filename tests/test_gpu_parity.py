@@ -289,3 +289,33 @@ def test_decode_larger_pool_custom_scale_and_side_stream():
             side.synchronize()
         compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
                 oo.reshape(-1, 128), ol.reshape(-1), "bf16", "decode scale/pad/stream %s" % opts)
+
+
+def test_selected_and_simulated_trees_parity():
+    """Trees that come out of the selection step: the kept leaves of config 3's last step,
+    and the last step of a synthetic search continued from the cost model's sets; decode
+    attention on both against the oracle."""
+    from workload import Tree, simulate_search
+    cfg = CONFIGS["c3_div"]
+    tree = make_tree(cfg)
+    r = np.random.default_rng(12)
+    w = ets.ets_rebase_weights(r.random(tree.n_leaves), tree.n_leaves, 0.2)
+    keep, info = ets.ets_select_leaves(tree.parent, tree.leaf_node, w,
+                                       r.integers(0, 8, tree.n_leaves), 1.5, 1.0)
+    assert info.optimal == 1 and 0 < keep.sum() < tree.n_leaves
+    pruned = Tree(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node[keep],
+                  tree.pool_tokens)
+
+    def sel(p, l, w_, c, lb, ld, nl):
+        return ets.ets_select_leaves(p, l, w_, c, lb, ld, nl)
+
+    sim = simulate_search("ets", 24, 6, 300, 20, 90, 3, lambda_b=1.5, lambda_d=1.0, select=sel,
+                          rebase=ets.ets_rebase_weights, node_limit=5000)["tree"]
+    for name, t in (("kept leaves", pruned), ("simulated search", sim)):
+        k, v, q = make_values_host(cfg, t)
+        oo, ol = oracle_full(cfg, t, k, v, q)
+        print("case", name, flush=True)
+        with make_ctx(cfg) as ctx:
+            out, lse, _ = gpu_attn(ctx, t, pool_to_device(k), pool_to_device(v), to_device(q))
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", name)
