@@ -208,6 +208,27 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
     return out, lse
 
 
+def tree_decode_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
+                           v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
+    """Decode attention over pools stored as E4M3 codes with one scale each:
+    K[t, h, :] = k_scale * value(k_codes[t, h, :]), V likewise with v_scale; q as bfloat16
+    bit patterns (uint16) or float32.  The definition is tree_decode_attn's on those K and
+    V.  Since the scores are linear in K and the output is linear in V, it is evaluated as
+    attention over the decoded codes with sm_scale * k_scale in place of sm_scale, and the
+    output times v_scale (lse needs nothing: it is taken over the scaled scores)."""
+    from .fp8 import decode_e4m3
+    k = decode_e4m3(k_codes)
+    v = decode_e4m3(v_codes)
+    q = np.asarray(q)
+    if q.dtype == np.uint16:
+        q = (q.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    base = float(sm_scale) if sm_scale > 0 else 1.0 / float(np.sqrt(np.float64(head_dim)))
+    out, lse = tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k, v,
+                                np.ascontiguousarray(q, dtype=np.float32), n_kv_heads, n_q_heads,
+                                head_dim, sm_scale=base * float(k_scale), rows=rows)
+    return out * float(v_scale), lse
+
+
 def prefill_q_ptr(n_tokens, leaf_node):
     """First query row of every leaf query in step prefill: int64 [L + 1], the prefix
     sums of the leaf nodes' lengths (every token of a leaf query's node is a query)."""

@@ -87,6 +87,30 @@ def test_c5_two_layers_sampled_parity():
                     cfg.dtype, "c5/layer%d" % layer)
 
 
+def test_c6_batched_searches_sampled_parity():
+    """Sixteen searches batched into one forest and one call (a serving system works on
+    several problems at once): sampled (leaf, head) rows from every search against the
+    oracle, and the plan's counts equal sixteen times a single search's structure."""
+    cfg = CONFIGS["c6_batch16"]
+    tree = make_tree(cfg)
+    assert int((tree.parent < 0).sum()) == cfg.trees and tree.n_leaves == cfg.trees * cfg.width
+    print("case c6 batch", flush=True)
+    kd, vd, qd = make_values_device(cfg, tree, "cuda:0", layers=1)
+    with make_ctx(cfg) as ctx:
+        out, lse, st = gpu_attn(ctx, tree, kd[0], vd[0], qd[0])
+    assert st.n_leaves == tree.n_leaves and st.unique_tokens == tree.pool_tokens
+    assert torch.isfinite(lse).all()
+    r = np.random.default_rng(6)
+    # three leaves of every search
+    leaves = (np.repeat(np.arange(cfg.trees), 3) * cfg.width
+              + r.integers(0, cfg.width, size=3 * cfg.trees)).astype(np.int32)
+    heads = r.integers(0, cfg.n_q_heads, size=leaves.size).astype(np.int32)
+    k, v, q = pool_to_host(kd[0]), pool_to_host(vd[0]), to_host_bits(qd[0])
+    oo, ol = oracle_rows(cfg, tree, k, v, q, leaves, heads)
+    compare(out.cpu().numpy()[leaves, heads], lse.cpu().numpy()[leaves, heads], oo, ol,
+            cfg.dtype, "c6")
+
+
 SHAPES = [(2, 8, 128, "bf16"), (1, 8, 64, "bf16"), (2, 2, 64, "f32"), (3, 6, 128, "f32"),
           (4, 4, 128, "bf16"), (1, 2, 64, "bf16")]
 

@@ -40,6 +40,7 @@ class TreeConfig:
     layers: int = 1
     store_dead: bool = True     # dead nodes own pool rows (False: they alias row 0)
     seed: int = 0
+    trees: int = 1              # independent searches (problems) batched into one forest
 
     @property
     def group(self) -> int:
@@ -64,6 +65,10 @@ CONFIGS = {
                          store_dead=False, seed=1004),
     "c5_stress": TreeConfig("c5_stress", 8, 32, 128, "bf16", 4096, 32, 64, 512, 512,
                             0.3, layers=32, store_dead=False, seed=1005),
+    # 16 searches of the c4 shape running side by side, as a serving system batches
+    # the problems it works on: one forest, one pool, one call
+    "c6_batch16": TreeConfig("c6_batch16", 8, 64, 128, "bf16", 2048, 24, 32, 256, 256, 0.3,
+                             layers=4, store_dead=False, seed=1006, trees=16),
 }
 
 
@@ -90,8 +95,24 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
 
 
 def make_tree(cfg: TreeConfig, seed: Optional[int] = None) -> Tree:
-    """Build the topology of `cfg` (see the module docstring for the recipe)."""
+    """Build the topology of `cfg` (see the module docstring for the recipe).  With
+    cfg.trees > 1 the result is a forest of that many independent searches (search t
+    drawn with seed + 7919 t), nodes and pool rows of one search after the other."""
     seed = cfg.seed if seed is None else seed
+    if cfg.trees > 1:
+        from dataclasses import replace
+        one = replace(cfg, trees=1)
+        parts = [make_tree(one, seed + 7919 * t) for t in range(cfg.trees)]
+        node0 = np.cumsum([0] + [p.n_nodes for p in parts])
+        row0 = np.cumsum([0] + [p.pool_tokens for p in parts])
+        return Tree(
+            np.concatenate([np.where(p.parent < 0, -1, p.parent + node0[t]).astype(np.int32)
+                            for t, p in enumerate(parts)]),
+            np.concatenate([p.tok_offset + row0[t] for t, p in enumerate(parts)]),
+            np.concatenate([p.n_tokens for p in parts]),
+            np.concatenate([(p.leaf_node + node0[t]).astype(np.int32)
+                            for t, p in enumerate(parts)]),
+            int(row0[-1]), np.concatenate([p.step for p in parts]))
     topo = _rng(seed, 0)
     lens = _rng(seed, 1)
 
@@ -211,6 +232,56 @@ def make_values_device(cfg: TreeConfig, tree: Tree, device, seed: Optional[int] 
     for l in range(layers):
         k[l].normal_(generator=g)
         v[l].normal_(generator=g)
+        q[l].normal_(generator=g)
+    return k, v, q
+
+
+def quantize_e4m3(x, scale: float):
+    """torch tensor (any float dtype) -> E4M3 codes (torch.uint8, same shape and device) of
+    x / scale: torch's own round-to-nearest conversion to float8_e4m3fn, so this module
+    holds no arithmetic of the format; magnitudes beyond 448 are clamped first (the
+    format has no infinity)."""
+    import torch
+    y = (x.to(torch.float32) / float(scale)).clamp_(-448.0, 448.0)
+    return y.to(torch.float8_e4m3fn).view(torch.uint8)
+
+
+def make_values_fp8_host(cfg: TreeConfig, tree: Tree, k_scale: float, v_scale: float,
+                         seed: Optional[int] = None, layer: int = 0):
+    """The values of make_values_host with K and V stored as E4M3 codes of K / k_scale and
+    V / v_scale: (k_codes, v_codes) uint8 [pool row, kv head, D], q bfloat16 bits."""
+    import torch
+    assert cfg.dtype == "bf16"
+    seed = cfg.seed if seed is None else seed
+    r = _rng(seed, 2 + layer)
+    shape = (tree.pool_tokens, cfg.n_kv_heads, cfg.head_dim)
+    k = r.standard_normal(shape, dtype=np.float32)
+    v = r.standard_normal(shape, dtype=np.float32)
+    q = r.standard_normal((tree.n_leaves, cfg.n_q_heads, cfg.head_dim), dtype=np.float32)
+    return (quantize_e4m3(torch.from_numpy(k), k_scale).numpy(),
+            quantize_e4m3(torch.from_numpy(v), v_scale).numpy(), to_bf16_bits(q))
+
+
+def make_values_fp8_device(cfg: TreeConfig, tree: Tree, device, k_scale: float, v_scale: float,
+                           seed: Optional[int] = None, layers: Optional[int] = None):
+    """Device-side generation: K, V uint8 E4M3 codes [layers, Hkv, pool_tokens, D] (the
+    library's layout) of N(0,1) draws divided by the scales, Q bfloat16 [layers, L, Hq, D]."""
+    import torch
+    seed = cfg.seed if seed is None else seed
+    layers = cfg.layers if layers is None else layers
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    shape = (cfg.n_kv_heads, tree.pool_tokens, cfg.head_dim)
+    k = torch.empty((layers,) + shape, dtype=torch.uint8, device=device)
+    v = torch.empty_like(k)
+    q = torch.empty((layers, tree.n_leaves, cfg.n_q_heads, cfg.head_dim),
+                    dtype=torch.bfloat16, device=device)
+    tmp = torch.empty(shape[1:], dtype=torch.float32, device=device)
+    for l in range(layers):
+        for dst, sc in ((k, k_scale), (v, v_scale)):
+            for h in range(cfg.n_kv_heads):
+                tmp.normal_(generator=g)
+                dst[l, h] = quantize_e4m3(tmp, sc)
         q[l].normal_(generator=g)
     return k, v, q
 
