@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--select", type=int, default=1,
                     help="1 = also run the ETS selection step on the tree's leaves and time "
                          "decode attention on the pruned tree (0 = skip)")
+    ap.add_argument("--variants", type=int, default=1,
+                    help="1 = also time decode attention over E4M3 K/V pools and with bf16 "
+                         "output on the same tree (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "scaling hardware byte counters when profiling)")
@@ -225,6 +228,82 @@ def main():
                 "speedup_tree_vs_flat": round(flat_ms / ms_per_step, 2),
                 "flat_over_unique_bytes": round(st.flat_kv_bytes / max(st.unique_kv_bytes, 1), 2)}
         log("flat baseline: %.3f ms/step -> tree is %.2fx faster" % (flat_ms, flat_ms / ms_per_step))
+
+    variants = None
+    fp8_check = None
+    if args.variants and cfg.dtype == "bf16" and d == 128:
+        # The same tree with K and V stored as E4M3 codes (half the bytes that bound the
+        # path), on 8 pools of their own, and the native pools again with bf16 output.
+        from workload import make_values_fp8_device
+        ks8, vs8 = 0.0123, 0.0217
+        n8 = 8
+        k8, v8, q8 = make_values_fp8_device(cfg, tree, dev, ks8, vs8, seed=cfg.seed + 8, layers=n8)
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, ks8, vs8)
+        st8 = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node, ets.ETS_PLAN_TREE)
+        ws8 = torch.empty(max(st8.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+
+        def run8(reps, o_, l_):
+            for _ in range(reps):
+                for p_ in range(n8):
+                    ctx.decode(k8[p_], v8[p_], tree.pool_tokens, q8[p_], o_[p_ % n_pools],
+                               l_[p_ % n_pools], ws8, ws8.numel(), stream.cuda_stream)
+
+        run8(1, out, lse)
+        torch.cuda.synchronize()
+        if args.cpu_seconds > 0:
+            fp8_check = (k8[0], v8[0], q8[0], out[0].clone(), lse[0].clone(), ks8, vs8)
+        t0 = time.perf_counter()
+        run8(3, out, lse)
+        torch.cuda.synchronize()
+        el8 = (time.perf_counter() - t0) / (3 * n8)
+        ctx.set_option("profile", 1)
+        ctx.profile_read()
+        run8(3, out, lse)
+        torch.cuda.synchronize()
+        pr8 = ctx.profile_read()
+        ctx.set_option("profile", 0)
+        us8 = pr8.cascade_ms / max(pr8.calls, 1) * 1e3
+        variants = {"fp8_kv": {
+            "format": "E4M3 codes, one scale per pool", "pools_rotated": n8,
+            "unique_kv_bytes": int(st8.unique_kv_bytes),
+            "us_per_layer": round(el8 * 1e6, 1),
+            "leaf_queries_per_s": round(L / el8, 1),
+            "speedup_vs_bf16_pools": round(ms_per_step / cfg.layers * 1e-3 / el8, 3),
+            "tree_attn_us": round(us8, 2),
+            "merge_us": round(pr8.merge_ms / max(pr8.calls, 1) * 1e3, 2),
+            "roofline": {"bound": "hbm", "kernel": "tree_attn_kernel<E4M3>",
+                         "achieved": round(st8.unique_kv_bytes / (us8 * 1e-6) / 1e9, 1),
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(st8.unique_kv_bytes / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "traffic": None, "avg_launch_us": round(us8, 2),
+                         "algorithmic_bytes_per_launch": int(st8.unique_kv_bytes)}}}
+        log("E4M3 pools: %.1f us per layer (%.2fx the bf16 pools' rate), tree_attn %.1f us = "
+            "%.0f GB/s of unique KV (%.1f%% of peak)" %
+            (el8 * 1e6, variants["fp8_kv"]["speedup_vs_bf16_pools"], us8,
+             variants["fp8_kv"]["roofline"]["achieved"],
+             variants["fp8_kv"]["roofline"]["frac"] * 100))
+        if fp8_check is None:
+            del k8, v8, q8
+        del ws8
+        # bf16 output on the native pools
+        ctx.set_kv_format(ets.ETS_KV_NATIVE)
+        stb = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node, ets.ETS_PLAN_TREE)
+        wsb = torch.empty(max(stb.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        o16 = torch.empty((L, hq, d), dtype=torch.bfloat16, device=dev)
+        ctx.set_option("out_bf16", 1)
+        ctx.set_option("profile", 1)
+        ctx.profile_read()
+        for p_ in range(min(8, n_pools)):
+            k_, v_, q_, _, l_ = pools[p_]
+            ctx.decode(k_, v_, tree.pool_tokens, q_, o16, l_, wsb, wsb.numel(), stream.cuda_stream)
+        torch.cuda.synchronize()
+        prb = ctx.profile_read()
+        ctx.set_option("profile", 0)
+        ctx.set_option("out_bf16", 0)
+        variants["bf16_out"] = {"merge_us": round(prb.merge_ms / max(prb.calls, 1) * 1e3, 2),
+                                "merge_us_fp32_out": kernel_us["merge"],
+                                "out_bytes": int(L * hq * d * 2)}
+        del o16, wsb
 
     decode_step = None
     if args.decode_tokens > 0:
@@ -461,6 +540,21 @@ def main():
                   "ok": bool(err_o <= tol and err_l <= tol)}
         log("oracle: %d rows in %.1f s on %d threads; parity out %.2e lse %.2e" %
             (n_rows, t_or, nthr, err_o, err_l))
+        if fp8_check is not None:
+            k8_, v8_, q8_, o8_, l8_, ks8, vs8 = fp8_check
+            n_s = 2 * nthr
+            lv8, hd8 = sample(n_s)
+            fo, fl = oracle.tree_decode_attn_fp8kv(
+                tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                k8_.cpu().numpy().transpose(1, 0, 2), v8_.cpu().numpy().transpose(1, 0, 2), ks8, vs8,
+                q8_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16),
+                cfg.n_kv_heads, hq, d, rows=(lv8, hd8))
+            e_o = float(np.abs(o8_.cpu().numpy()[lv8, hd8].astype(np.float64) - fo).max())
+            e_l = float(np.abs(l8_.cpu().numpy()[lv8, hd8].astype(np.float64) - fl).max())
+            variants["fp8_kv"]["parity_sample"] = {"rows": n_s, "out_max_abs": e_o,
+                                                   "lse_max_abs": e_l, "tol_abs": tol,
+                                                   "ok": bool(e_o <= tol and e_l <= tol)}
+            log("oracle (E4M3 pools): %d rows; parity out %.2e lse %.2e" % (n_s, e_o, e_l))
         if pre_check is not None:
             qp, outp0, lsep0 = pre_check
             qph = qp.view(torch.int16).cpu().numpy().view(np.uint16)
@@ -509,6 +603,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "flat_baseline": flat,
+        "variants": variants,
         "decode_step": decode_step,
         "prefill": prefill,
         "selector": selector,

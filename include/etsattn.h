@@ -163,11 +163,11 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
  * ets_kv_append writes, for every distinct node of leaf_node, one new row of K and V
  * at pool row tok_offset[node] + n_tokens[node] (the plan's current lengths), which
  * the caller must have reserved for that node.
- *   k_pool, v_pool  DEVICE, as in ets_tree_decode_attn, written
+ *   k_pool, v_pool  DEVICE, as in ets_tree_decode_attn (same element size), written
  *   pool_tokens     rows per head plane, as in ets_tree_decode_attn; must exceed
  *                   every written row, else ETS_ERR_INVALID_ARG and nothing is written
- *   k_new, v_new    DEVICE, [n_leaves][n_kv_heads][head_dim] of shape.dtype, 16-byte
- *                   aligned: row l is the new token of leaf query l; when several leaf
+ *   k_new, v_new    DEVICE, [n_leaves][n_kv_heads][head_dim] of the pools' element type,
+ *                   16-byte aligned: row l is the new token of leaf query l; when several leaf
  *                   queries sit on one node, the first of them supplies the row
  * Asynchronous on hip_stream; no allocation.
  *
@@ -198,19 +198,45 @@ ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned);
  *   "mfma"           1 (default) = matrix-core kernel for bf16 pools with
  *                    head_dim 128; 0 = vector-ALU kernel for every shape (each
  *                    leaf then reads its whole chain itself)
+ *   "out_bf16"       1 = ets_tree_decode_attn writes `out` as bfloat16 (the merged fp32
+ *                    result rounded to nearest even), for a consumer that takes the next
+ *                    projection's input in bf16; 0 (default) = fp32.  Effective from
+ *                    the next decode call; lse stays fp32
  *   "profile"        1 = record kernel times (see ets_profile_read), 0 = off
  * Unknown key or negative value: ETS_ERR_INVALID_ARG. */
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 
+/* Storage format of the K/V pools.  The search is bound by the bytes of KV state that
+ * every generation step reads (ETS paper Sec. 1; Sec. 3, factor 1); a cache that stores
+ * K and V in 8 bits halves them.
+ *   ETS_KV_NATIVE    pools hold shape.dtype elements (default)
+ *   ETS_KV_FP8_E4M3  pools hold one byte per element: codes of the OCP 8-bit floating
+ *                    point format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ *                    bits; no infinities; S.1111.111 is NaN), and
+ *                        K[t,h,d] = k_scale * value(k_code),  V[t,h,d] = v_scale * value(v_code)
+ *                    with one positive finite scale per pool.  Layout, row numbering and
+ *                    alignment are as for native pools with 1-byte elements; q stays
+ *                    bf16.  Only for bf16 contexts with head_dim 128 (ETS_ERR_UNSUPPORTED
+ *                    otherwise) and with the "mfma" option on (else ets_tree_decode_attn
+ *                    returns ETS_ERR_UNSUPPORTED).  ets_kv_append then copies 1-byte
+ *                    elements (k_new, v_new hold codes); step prefill is not available
+ *                    (ets_plan_prefill returns ETS_ERR_UNSUPPORTED).
+ * The scales are ignored for ETS_KV_NATIVE.  The call drops the current plans: run
+ * ets_plan again (byte statistics and work-item sizes follow the element size). */
+typedef enum { ETS_KV_NATIVE = 0, ETS_KV_FP8_E4M3 = 1 } ets_kv_format;
+ets_status ets_set_kv_format(ets_ctx* ctx, int kv_format /* ets_kv_format */, float k_scale,
+                             float v_scale);
+
 /* One layer of decode attention for every leaf query of the planned tree.
- *   k_pool, v_pool  DEVICE, [n_kv_heads][pool_tokens][head_dim] of shape.dtype,
- *                   16-byte aligned: one plane of pool_tokens rows per kv head, so
+ *   k_pool, v_pool  DEVICE, [n_kv_heads][pool_tokens][head_dim] of shape.dtype (of E4M3
+ *                   codes after ets_set_kv_format), 16-byte aligned: one plane of pool_tokens rows per kv head, so
  *                   that the rows of a node are contiguous within a head (pool row
  *                   t of head h starts at element (h * pool_tokens + t) * head_dim)
  *   pool_tokens     rows per head plane of BOTH pools, i.e. the plane stride (not
  *                   merely a bound); >= stats.min_pool_tokens, else ETS_ERR_BAD_TREE
  *   q               DEVICE, [n_leaves][n_q_heads][head_dim] of shape.dtype, 16-byte aligned
- *   out             DEVICE, [n_leaves][n_q_heads][head_dim] float
+ *   out             DEVICE, [n_leaves][n_q_heads][head_dim] float (bfloat16 with the
+ *                   "out_bf16" option), 16-byte aligned
  *   lse             DEVICE, [n_leaves][n_q_heads] float
  *   workspace       DEVICE, >= stats.workspace_bytes, 16-byte aligned, contents
  *                   undefined before and after; may be NULL when that is 0
@@ -221,7 +247,7 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
  * of calls (layers, decode steps) while the tree is unchanged.  The result is
  * bitwise reproducible from run to run (no floating-point atomics). */
 ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
-                                int64_t pool_tokens, const void* q, float* out, float* lse,
+                                int64_t pool_tokens, const void* q, void* out, float* lse,
                                 void* workspace, int64_t workspace_bytes, void* hip_stream);
 
 /* Kernel times for benchmarks.  After ets_set_option(ctx, "profile", 1) every

@@ -10,6 +10,7 @@ import numpy as np
 
 ETS_F32, ETS_BF16 = 0, 1
 ETS_PLAN_TREE, ETS_PLAN_FLAT = 0, 1
+ETS_KV_NATIVE, ETS_KV_FP8_E4M3 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libetsattn.so")
@@ -104,6 +105,8 @@ def load_library():
     lib.ets_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
     lib.ets_tree_decode_attn.restype = C.c_int
     lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
+    lib.ets_set_kv_format.restype = C.c_int
+    lib.ets_set_kv_format.argtypes = [vp, C.c_int, C.c_float, C.c_float]
     lib.ets_kv_append.restype = C.c_int
     lib.ets_kv_append.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
     lib.ets_plan_advance.restype = C.c_int
@@ -161,6 +164,11 @@ def ets_destroy(ctx):
 
 def ets_set_option(ctx, key: str, value: int):
     _check(load_library().ets_set_option(ctx, key.encode(), int(value)), "ets_set_option")
+
+
+def ets_set_kv_format(ctx, kv_format: int, k_scale: float = 1.0, v_scale: float = 1.0):
+    _check(load_library().ets_set_kv_format(ctx, int(kv_format), float(k_scale), float(v_scale)),
+           "ets_set_kv_format")
 
 
 def _tree_struct(parent, tok_offset, n_tokens, leaf_node):
@@ -363,6 +371,9 @@ class Context:
 
     def set_option(self, key, value):
         ets_set_option(self._ctx, key, value)
+
+    def set_kv_format(self, kv_format, k_scale=1.0, v_scale=1.0):
+        ets_set_kv_format(self._ctx, kv_format, k_scale, v_scale)
 
     def plan(self, parent, tok_offset, n_tokens, leaf_node, mode=ETS_PLAN_TREE) -> EtsStats:
         ets_plan(self._ctx, parent, tok_offset, n_tokens, leaf_node, mode)

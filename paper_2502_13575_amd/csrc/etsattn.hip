@@ -24,6 +24,10 @@ struct ets_ctx {
     float scale = 0.f;
     int device = -1;
     PlanOptions opt;
+    // variants: pools of E4M3 codes with one scale each; bf16 output
+    int kv_format = ETS_KV_NATIVE;
+    float k_scale = 1.f, v_scale = 1.f;
+    bool out_bf16 = false;
     Plan plan;
     // device copies of the plan's index arrays, carved out of one allocation
     char* d_buf = nullptr;
@@ -150,7 +154,7 @@ ets_status upload_plan(ets_ctx* c) {
 struct LaunchArgs {
     const void *k, *v, *q;
     int64_t pool_tokens;
-    float* out;
+    void* out;
     float* lse;
     float* ws_o;
     float2* ws_ml;
@@ -190,12 +194,18 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     const int64_t n_wgs = n_single + (n_items - n_single + 3) / 4;
     for (int64_t y0 = 0; y0 < n_wgs; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
-        hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0,
-                           a.stream, static_cast<const bf16_t*>(a.k),
-                           static_cast<const bf16_t*>(a.v), a.pool_tokens,
-                           static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0, (int)n_single, (int)n_items,
-                           c->d_ent_order, c->d_ent_base, g_shift,
-                           c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+        if (c->kv_format == ETS_KV_FP8_E4M3)
+            hipLaunchKernelGGL(tree_attn_kernel<true>, dim3((unsigned)c->shape.n_kv_heads, ny),
+                               dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
+                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
+                               (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
+                               c->scale * c->k_scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+        else
+            hipLaunchKernelGGL(tree_attn_kernel<false>, dim3((unsigned)c->shape.n_kv_heads, ny),
+                               dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
+                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
+                               (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
+                               c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
     }
 }
 
@@ -266,14 +276,24 @@ void launch_all(ets_ctx* c, const LaunchArgs& a) {
     mark(c, 2, a.stream);
     const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
     const unsigned grid = (unsigned)((pairs + 3) / 4);
-    if (c->shape.head_dim == 128)
-        hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, (int)c->plan.stats.n_leaves, c->shape.n_q_heads,
-                           a.ws_o, a.ws_ml, a.out, a.lse);
+    const float out_scale = c->kv_format == ETS_KV_FP8_E4M3 ? c->v_scale : 1.f;
+    const int n_leaves = (int)c->plan.stats.n_leaves;
+    if (c->shape.head_dim == 128 && c->out_bf16)
+        hipLaunchKernelGGL((merge_kernel<128, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
+                           static_cast<bf16_t*>(a.out), a.lse, out_scale);
+    else if (c->shape.head_dim == 128)
+        hipLaunchKernelGGL((merge_kernel<128, float>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
+                           static_cast<float*>(a.out), a.lse, out_scale);
+    else if (c->out_bf16)
+        hipLaunchKernelGGL((merge_kernel<64, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
+                           static_cast<bf16_t*>(a.out), a.lse, out_scale);
     else
-        hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, (int)c->plan.stats.n_leaves, c->shape.n_q_heads,
-                           a.ws_o, a.ws_ml, a.out, a.lse);
+        hipLaunchKernelGGL((merge_kernel<64, float>), dim3(grid), dim3(256), 0, a.stream,
+                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
+                           static_cast<float*>(a.out), a.lse, out_scale);
     mark(c, 3, a.stream);
     if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
 }
@@ -331,11 +351,31 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
         ctx->opt.cascade_rows = value;
     } else if (!std::strcmp(key, "wave_items")) ctx->opt.wave_items = value;
     else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
+    else if (!std::strcmp(key, "out_bf16")) ctx->out_bf16 = value != 0;
     else if (!std::strcmp(key, "profile")) {
         if (value != 0 && ctx->device < 0) return ETS_ERR_HIP;
         ctx->profile = value != 0;
     }
     else return ETS_ERR_INVALID_ARG;
+    return ETS_OK;
+}
+
+ets_status ets_set_kv_format(ets_ctx* ctx, int kv_format, float k_scale, float v_scale) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (kv_format != ETS_KV_NATIVE && kv_format != ETS_KV_FP8_E4M3) return ETS_ERR_INVALID_ARG;
+    if (kv_format == ETS_KV_FP8_E4M3) {
+        if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) ||
+            !std::isfinite(v_scale))
+            return ETS_ERR_INVALID_ARG;
+        if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
+    }
+    ctx->kv_format = kv_format;
+    ctx->k_scale = kv_format == ETS_KV_FP8_E4M3 ? k_scale : 1.f;
+    ctx->v_scale = kv_format == ETS_KV_FP8_E4M3 ? v_scale : 1.f;
+    ctx->opt.kv_elem_bytes = kv_format == ETS_KV_FP8_E4M3 ? 1 : 0;
+    // byte counts and item sizes of a plan depend on the element size
+    ctx->plan.valid = false;
+    ctx->prefill.valid = false;
     return ETS_OK;
 }
 
@@ -405,7 +445,8 @@ ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_
     if (!k_pool || !v_pool || !k_new || !v_new) return ETS_ERR_INVALID_ARG;
     // every node's next row has to exist in the pool
     if (pool_tokens < p.stats.min_pool_tokens + 1) return ETS_ERR_INVALID_ARG;
-    const int64_t esz = ctx->shape.dtype == ETS_F32 ? 4 : 2;
+    const int64_t esz =
+        ctx->kv_format == ETS_KV_FP8_E4M3 ? 1 : ctx->shape.dtype == ETS_F32 ? 4 : 2;
     const int head_bytes = (int)(ctx->shape.head_dim * esz);
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return ETS_ERR_HIP;
@@ -481,7 +522,7 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
 }
 
 ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
-                                int64_t pool_tokens, const void* q, float* out, float* lse,
+                                int64_t pool_tokens, const void* q, void* out, float* lse,
                                 void* workspace, int64_t workspace_bytes, void* hip_stream) {
     if (!ctx) return ETS_ERR_INVALID_ARG;
     if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
@@ -491,6 +532,9 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
     if (!q || !out || !lse || pool_tokens < 0 || workspace_bytes < 0) return ETS_ERR_INVALID_ARG;
     if (st.unique_tokens > 0 && (!k_pool || !v_pool)) return ETS_ERR_INVALID_ARG;
     if (pool_tokens < st.min_pool_tokens) return ETS_ERR_BAD_TREE;
+    // E4M3 pools are read by the matrix-core kernel only
+    if (ctx->kv_format == ETS_KV_FP8_E4M3 && !ctx->plan.stream_items.empty())
+        return ETS_ERR_UNSUPPORTED;
     if (workspace_bytes < st.workspace_bytes || (st.workspace_bytes > 0 && !workspace))
         return ETS_ERR_WORKSPACE;
     if (misaligned(k_pool) || misaligned(v_pool) || misaligned(q) || misaligned(out) ||
@@ -521,6 +565,7 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
 ets_status ets_plan_prefill(ets_ctx* ctx, const ets_tree* tree) {
     if (!ctx || !tree) return ETS_ERR_INVALID_ARG;
     if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
+    if (ctx->kv_format != ETS_KV_NATIVE) return ETS_ERR_UNSUPPORTED;
     ets_status s = build_prefill_plan(ctx->shape, *tree, ctx->prefill);
     if (s != ETS_OK) return s;
     if (ctx->device >= 0) {

@@ -5,20 +5,28 @@
 // out = sum o_i w_i / l*,  lse = (m* + log2 l*) ln 2.  The partials of a leaf
 // are consecutive slots and are combined in slot order, so the result does not
 // depend on scheduling.  A leaf without partials (empty chain) gets out = 0,
-// lse = -inf.
+// lse = -inf.  out may be written as fp32 or rounded to bf16 (nearest even), and is
+// multiplied by out_scale first (the scale of a quantised V pool; 1 otherwise).
 #pragma once
 
 #include "device_utils.hpp"
 
 namespace ets {
 
-template <int D>
+// float -> bfloat16 bits, round to nearest even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+template <int D, typename OutT>
 __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ part_base,
                                                     int n_leaves, int n_q_heads,
                                                     const float* __restrict__ ws_o,
                                                     const float2* __restrict__ ws_ml,
-                                                    float* __restrict__ out,
-                                                    float* __restrict__ lse) {
+                                                    OutT* __restrict__ out,
+                                                    float* __restrict__ lse, float out_scale) {
     constexpr int EPL = D / 64;  // floats per lane
     struct alignas(4 * EPL) RowPiece {
         float f[EPL];
@@ -82,9 +90,15 @@ __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ 
     }
     const bool empty = p1 == p0;
     const float inv = empty ? 0.f : 1.f / ls;
-    float* dst = out + pair * D + lane * EPL;
+    if constexpr (sizeof(OutT) == 4) {
+        float* dst = reinterpret_cast<float*>(out) + pair * D + lane * EPL;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) dst[i] = acc[i] * inv;
+        for (int i = 0; i < EPL; ++i) dst[i] = acc[i] * inv * out_scale;
+    } else {
+        uint16_t* dst = reinterpret_cast<uint16_t*>(out) + pair * D + lane * EPL;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) dst[i] = f32_to_bf16_rne(acc[i] * inv * out_scale);
+    }
     if (lane == 0)
         lse[pair] = empty ? -INFINITY : (ms + __builtin_amdgcn_logf(ls)) * 0.6931471805599453f;
 }

@@ -136,7 +136,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                  Plan& p) {
     const int32_t N = tree.n_nodes, L = tree.n_leaves;
     const int32_t G = shape.n_q_heads / shape.n_kv_heads;
-    const int64_t esz = shape.dtype == ETS_F32 ? 4 : 2;
+    const int64_t esz = opt.kv_elem_bytes > 0 ? opt.kv_elem_bytes : shape.dtype == ETS_F32 ? 4 : 2;
 
     p.mode = mode;
     p.parent.assign(tree.parent, tree.parent + N);

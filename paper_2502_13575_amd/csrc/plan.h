@@ -56,6 +56,7 @@ struct AdvEntry {
 };
 
 struct PlanOptions {
+    int64_t kv_elem_bytes = 0;       // bytes per pool element; 0 = by the shape's dtype
     int64_t stream_chunk = 0;        // 0 = auto
     int64_t cascade_chunk = 0;       // 0 = auto
     int64_t cascade_rows = 64;       // query rows per shared work item (16, 32 or 64)

@@ -43,6 +43,11 @@
 //                  {4kg..4kg+3} of both 16-token halves; V^T is brought to that
 //                  slot order by a transpose in registers of coalesced 16-byte
 //                  row pieces before it is staged.
+// Pools of E4M3 codes (template parameter FP8; one scale per pool, applied by the
+// caller to the score scale and to the merged output): rows are 128 bytes, a lane
+// fetches the same 8 elements with an 8-byte load, and the codes are widened to bf16
+// (exactly: 4 significant bits) when the tile is staged; everything after the staging
+// is the bf16 path unchanged.
 // Loads of the next tile are in flight while the current one is computed.
 // The result per query row is the unnormalised partial (o, m, l), m in log2
 // units, merged later along each leaf's chain.
@@ -66,6 +71,41 @@ __device__ __forceinline__ f16x8_t as_f16x8(u32x4_t v) { return __builtin_bit_ca
 __device__ __forceinline__ u32x4_t load16(const void* p) {
     return *reinterpret_cast<const u32x4_t*>(p);
 }
+// Eight E4M3 codes (two dwords) -> eight bf16 values, element order kept.  Every E4M3
+// value is a bf16 value, so the float -> bf16 conversion (one packed instruction per
+// pair) does not round.
+__device__ __forceinline__ u32x4_t e4m3x8_to_bf16x8(u32x2_t r) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    u32x4_t o;
+#pragma unroll
+    for (int dw = 0; dw < 2; ++dw) {
+        const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)r[dw], false);  // bytes 0, 1
+        const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)r[dw], true);   // bytes 2, 3
+        o[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+        o[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+    }
+    return o;
+}
+__device__ __forceinline__ u32x4_t widen_raw(u32x4_t r) { return r; }
+__device__ __forceinline__ u32x4_t widen_raw(u32x2_t r) { return e4m3x8_to_bf16x8(r); }
+template <bool FP8>
+__device__ __forceinline__ std::conditional_t<FP8, u32x2_t, u32x4_t> load_row_piece(
+    __amdgpu_buffer_rsrc_t rsrc, uint32_t voff, int soff, std::integral_constant<int, 0>) {
+    if constexpr (FP8)
+        return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, soff, 0));
+    else
+        return __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 0));
+}
+template <bool FP8>
+__device__ __forceinline__ std::conditional_t<FP8, u32x2_t, u32x4_t> load_row_piece(
+    __amdgpu_buffer_rsrc_t rsrc, uint32_t voff, int soff, std::integral_constant<int, 2>) {
+    if constexpr (FP8)
+        return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, soff, 2));
+    else
+        return __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2));
+}
+
 constexpr int kTreeAttnRowsPerItem = 64;  // 4 waves x 16 rows
 constexpr int kTreeAttnMaxSteps = 256;    // steps per work item (planner's cap)
 constexpr int kTreeAttnKRow = 17;         // 16-byte units per padded K row in LDS (272 bytes)
@@ -175,8 +215,9 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
     lsum += psum;
 }
 
+template <bool FP8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
-    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t pool_tokens,
+    const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
     const CascadeItem* __restrict__ items, int wg_base, int n_single, int n_items,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
@@ -226,21 +267,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const float raise_margin = 8.0f / scale_log2e;  // raw-score distance of 2^8 in weight
 
     // wave w fetches half hw of step 2 tile + sw of every tile
-    u32x4_t kraw[4], vraw[4];
-    constexpr uint32_t stride_b = D * 2;  // bytes between the tokens of a head plane
+    std::conditional_t<FP8, u32x2_t, u32x4_t> kraw[4], vraw[4];
+    constexpr uint32_t stride_b = FP8 ? D : D * 2;  // bytes between the tokens of a head plane
+    constexpr uint32_t piece_b = FP8 ? 8 : 16;      // bytes of a lane's 8 elements
     const int64_t plane = (int64_t)h * pool_tokens;  // first row of this kv head
     // K: token 16 hw + 4 i + b;  V: contraction slot 4 hw + j of group b = token 16 hw + 4 b + j
-    const uint32_t k_lane_off = (uint32_t)(16 * hw + b) * stride_b + a * 16;
-    const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + a * 16;
+    const uint32_t k_lane_off = (uint32_t)(16 * hw + b) * stride_b + a * piece_b;
+    const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + a * piece_b;
     // Buffer loads: a step's rows are addressed through a descriptor that covers exactly
     // the step (base = its first row at this kv head, size = n rows), so a load is a
     // scalar descriptor plus a 32-bit lane offset, and rows past the end of a ragged step
     // read as zero instead of needing clamped addresses (they are masked later).
     auto issue_loads = [&](const Run& sd, auto aux_tag) {
         // cache policy of the loads: 2 = non-temporal, for rows that no other item reads
-        constexpr int kAux = decltype(aux_tag)::value;
         if (sd.n > load_min) {
-            const int64_t base = (plane + sd.tok) * (int64_t)D * 2;
+            const int64_t base = (plane + sd.tok) * (int64_t)stride_b;
             char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;  // uniform
             char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
             const int bytes = sd.n * (int)stride_b;
@@ -250,21 +291,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                 // full step: every row is in range; the row stepping rides in the scalar offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                              kr, k_lane_off, 4 * i * (int)stride_b, kAux));
-                    vraw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                              vr, v_lane_off, i * (int)stride_b, kAux));
+                    kraw[i] = load_row_piece<FP8>(kr, k_lane_off, 4 * i * (int)stride_b, aux_tag);
+                    vraw[i] = load_row_piece<FP8>(vr, v_lane_off, i * (int)stride_b, aux_tag);
                 }
             } else {
                 // ragged step: the whole offset is in the range-checked lane offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = __builtin_bit_cast(
-                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0, kAux));
-                    vraw[i] = __builtin_bit_cast(
-                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     vr, v_lane_off + (uint32_t)i * stride_b, 0, kAux));
+                    kraw[i] = load_row_piece<FP8>(kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0,
+                                                  aux_tag);
+                    vraw[i] = load_row_piece<FP8>(vr, v_lane_off + (uint32_t)i * stride_b, 0,
+                                                  aux_tag);
                 }
             }
         }
@@ -329,8 +366,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         // ---- A small item walked by this wave alone: 16-token units in order (unit u =
         // half u & 1 of step u >> 1) through the wave's own LDS region, next unit's loads
         // in flight while the current one is computed; no fold, no workgroup barrier.
-        const uint32_t k_off0 = (uint32_t)b * stride_b + a * 16;        // K row b (+ 4 i)
-        const uint32_t v_off0 = (uint32_t)(4 * b) * stride_b + a * 16;  // V row 4 b (+ i)
+        const uint32_t k_off0 = (uint32_t)b * stride_b + a * piece_b;        // K row b (+ 4 i)
+        const uint32_t v_off0 = (uint32_t)(4 * b) * stride_b + a * piece_b;  // V row 4 b (+ i)
         u32x4_t* ksw = smem + w * (16 * KROW + 256);
         u32x2_t* vsw = reinterpret_cast<u32x2_t*>(ksw + 16 * KROW);
         auto unit_rows = [&](int u, int64_t& tok) {
@@ -340,7 +377,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         };
         auto issue_unit = [&](int64_t tok, int n) {
             if (n > 0) {
-                const int64_t base = (plane + tok) * (int64_t)D * 2;
+                const int64_t base = (plane + tok) * (int64_t)stride_b;
                 char* kb = const_cast<char*>(reinterpret_cast<const char*>(k_pool)) + base;
                 char* vb = const_cast<char*>(reinterpret_cast<const char*>(v_pool)) + base;
                 const __amdgpu_buffer_rsrc_t kr =
@@ -349,25 +386,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                     __builtin_amdgcn_make_buffer_rsrc(vb, 0, n * (int)stride_b, 0x00020000);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = __builtin_bit_cast(
-                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     kr, k_off0 + (uint32_t)(4 * i) * stride_b, 0, 2));
-                    vraw[i] = __builtin_bit_cast(
-                        u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                     vr, v_off0 + (uint32_t)i * stride_b, 0, 2));
+                    kraw[i] = load_row_piece<FP8>(kr, k_off0 + (uint32_t)(4 * i) * stride_b, 0,
+                                                  std::integral_constant<int, 2>{});
+                    vraw[i] = load_row_piece<FP8>(vr, v_off0 + (uint32_t)i * stride_b, 0,
+                                                  std::integral_constant<int, 2>{});
                 }
             }
         };
         auto stage_own = [&](int n) {
             if (n > 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = kraw[i];
+                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = widen_raw(kraw[i]);
+                const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
+                                       widen_raw(vraw[3])};
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
                     const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
                     u32x2_t t;
-                    t[0] = __builtin_amdgcn_perm(vraw[1][x >> 1], vraw[0][x >> 1], sel);
-                    t[1] = __builtin_amdgcn_perm(vraw[3][x >> 1], vraw[2][x >> 1], sel);
+                    t[0] = __builtin_amdgcn_perm(vw[1][x >> 1], vw[0][x >> 1], sel);
+                    t[1] = __builtin_amdgcn_perm(vw[3][x >> 1], vw[2][x >> 1], sel);
                     vsw[x * 64 + lane] = t;
                 }
             }
@@ -453,7 +490,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     auto stage = [&](const Run& sd) {
         if (sd.n > 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = kraw[i];
+            for (int i = 0; i < 4; ++i)
+                ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = widen_raw(kraw[i]);
+            const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
+                                   widen_raw(vraw[3])};
             // This half's four contraction slots of every V^T fragment (8 of its 16
             // bytes), converted to fp16 for the P V product once for all row blocks:
             // element x of the lane's 16-byte piece, tokens 4 b .. 4 b + 3.
@@ -462,13 +502,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             for (int j = 0; j < 4; ++j) {
                 u32x2_t te, to;
                 te[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_lo(vraw[0][j]), bf16_lo(vraw[1][j])));
+                                                         bf16_lo(vw[0][j]), bf16_lo(vw[1][j])));
                 te[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_lo(vraw[2][j]), bf16_lo(vraw[3][j])));
+                                                         bf16_lo(vw[2][j]), bf16_lo(vw[3][j])));
                 to[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_hi(vraw[0][j]), bf16_hi(vraw[1][j])));
+                                                         bf16_hi(vw[0][j]), bf16_hi(vw[1][j])));
                 to[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_hi(vraw[2][j]), bf16_hi(vraw[3][j])));
+                                                         bf16_hi(vw[2][j]), bf16_hi(vw[3][j])));
                 vs2[((sw * 8 + 2 * j) * 64 + lane) * 2 + hw] = te;
                 vs2[((sw * 8 + 2 * j + 1) * 64 + lane) * 2 + hw] = to;
             }
@@ -520,13 +560,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         auto stage_unit = [&](const Run& sd) {
             if (sd.n > 16 * hw) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = kraw[i];
+                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = widen_raw(kraw[i]);
+                const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
+                                       widen_raw(vraw[3])};
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
                     const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
                     u32x2_t t;
-                    t[0] = __builtin_amdgcn_perm(vraw[1][x >> 1], vraw[0][x >> 1], sel);
-                    t[1] = __builtin_amdgcn_perm(vraw[3][x >> 1], vraw[2][x >> 1], sel);
+                    t[0] = __builtin_amdgcn_perm(vw[1][x >> 1], vw[0][x >> 1], sel);
+                    t[1] = __builtin_amdgcn_perm(vw[3][x >> 1], vw[2][x >> 1], sel);
                     vsw[x * 64 + lane] = t;
                 }
             }

@@ -34,7 +34,7 @@ def _chain_rows(t, optr, onodes, l):
                            for n in nodes]).astype(np.int64)
 
 
-def _check_plan_against_oracle(ctx, t, mode, leaves=None):
+def _check_plan_against_oracle(ctx, t, mode, leaves=None, esz=None):
     st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, mode)
     ost = oracle.tree_stats(t.parent, t.n_tokens, t.leaf_node)
     assert st.unique_tokens == ost["unique_tokens"]
@@ -52,7 +52,7 @@ def _check_plan_against_oracle(ctx, t, mode, leaves=None):
         total_partials += npart
     if leaves is None:
         assert total_partials == st.n_partials
-    esz = 4 if ctx.shape.dtype == ets.ETS_F32 else 2
+    esz = esz or (4 if ctx.shape.dtype == ets.ETS_F32 else 2)
     assert st.unique_kv_bytes == st.unique_tokens * 2 * ctx.shape.n_kv_heads * ctx.shape.head_dim * esz
     assert st.workspace_bytes == st.n_partials * ctx.shape.n_q_heads * (ctx.shape.head_dim + 2) * 4
     return st
@@ -268,3 +268,44 @@ def test_advance_and_append_error_paths():
         with pytest.raises(ets.EtsError) as e:
             ctx.kv_append(None, None, 0, None, None)
         assert e.value.status == 6
+
+
+def test_kv_format_host_logic():
+    """E4M3 pools: accepted only where the matrix-core kernel runs, the plans are dropped,
+    byte statistics follow the 1-byte elements, the indexing does not change, and step
+    prefill is refused."""
+    cfg = CONFIGS["c3_pruned"]
+    t = make_tree(cfg)
+    with _ctx(cfg) as ctx:
+        st2 = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        for bad in [(ets.ETS_KV_FP8_E4M3, 0.0, 1.0), (ets.ETS_KV_FP8_E4M3, 1.0, -2.0),
+                    (ets.ETS_KV_FP8_E4M3, float("inf"), 1.0), (ets.ETS_KV_FP8_E4M3, float("nan"), 1.0),
+                    (7, 1.0, 1.0)]:
+            with pytest.raises(ets.EtsError) as e:
+                ctx.set_kv_format(*bad)
+            assert e.value.status == 1
+        assert ctx.stats().unique_kv_bytes == st2.unique_kv_bytes      # nothing changed so far
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, 0.02, 0.03)
+        with pytest.raises(ets.EtsError) as e:
+            ctx.stats()
+        assert e.value.status == 6                                     # plan dropped
+        with pytest.raises(ets.EtsError) as e:
+            ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert e.value.status == 4
+        st1 = _check_plan_against_oracle(ctx, t, ets.ETS_PLAN_TREE,
+                                         list(range(0, t.n_leaves, 4)), esz=1)
+        assert st1.unique_tokens == st2.unique_tokens
+        assert 2 * st1.unique_kv_bytes == st2.unique_kv_bytes
+        assert 2 * st1.flat_kv_bytes == st2.flat_kv_bytes
+        assert st1.unique_kv_bytes == st1.unique_tokens * 2 * cfg.n_kv_heads * cfg.head_dim
+        ctx.set_kv_format(ets.ETS_KV_NATIVE)
+        st3 = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert st3.unique_kv_bytes == st2.unique_kv_bytes
+        ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+    for shape in [(2, 4, 64, ets.ETS_BF16), (2, 4, 128, ets.ETS_F32)]:
+        with _ctx(shape) as ctx:
+            with pytest.raises(ets.EtsError) as e:
+                ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, 1.0, 1.0)
+            assert e.value.status == 4
+            ctx.set_kv_format(ets.ETS_KV_NATIVE)
+            ctx.set_option("out_bf16", 1)
