@@ -23,6 +23,7 @@ MFMA_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 / fp16 matrix-core peak, pub
 
 # sources whose change invalidates a stored counter reading, per kernel
 TRAFFIC_SOURCES = {"tree_attn": ("tree_attn_kernel.hpp", "plan.cpp"),
+                   "tree_attn_e4m3": ("tree_attn_kernel.hpp", "plan.cpp"),
                    "prefill_attn": ("prefill_attn_kernel.hpp", "prefill_plan.cpp")}
 
 
@@ -275,7 +276,8 @@ def main():
                          "achieved": round(st8.unique_kv_bytes / (us8 * 1e-6) / 1e9, 1),
                          "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(st8.unique_kv_bytes / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                         "traffic": None, "avg_launch_us": round(us8, 2),
+                         "traffic": measured_traffic(cfg.name, "tree_attn_e4m3"),
+                         "avg_launch_us": round(us8, 2),
                          "algorithmic_bytes_per_launch": int(st8.unique_kv_bytes)}}}
         log("E4M3 pools: %.1f us per layer (%.2fx the bf16 pools' rate), tree_attn %.1f us = "
             "%.0f GB/s of unique KV (%.1f%% of peak)" %

@@ -263,7 +263,9 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // time the whole call is expected to take: the larger of the HBM time of the
     // unique bytes (at ~5.5 TB/s) and the modelled work spread over 1024 resident
     // workgroups; no single item should take more than a third of it
-    const int64_t hbm_ns = st.unique_kv_bytes / 5500;
+    // (1-byte pools are budgeted like 2-byte ones: their launch is bound by the number
+    // of loads, not by their bytes, and finer items would only add partial results)
+    const int64_t hbm_ns = st.unique_kv_bytes * (esz < 2 ? 2 : 1) / 5500;
     const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 1024) / 3, 4 * t_mem);
 
     int64_t scap = opt.stream_chunk;
