@@ -343,3 +343,59 @@ def test_selected_and_simulated_trees_parity():
             out, lse, _ = gpu_attn(ctx, t, pool_to_device(k), pool_to_device(v), to_device(q))
         compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
                 oo.reshape(-1, 128), ol.reshape(-1), "bf16", name)
+
+
+def test_decode_and_prefill_under_graph_capture():
+    """The calls only enqueue kernels (no allocation, no synchronisation, nothing cleared
+    with a memset), so a caller may capture them into a HIP graph: several layers of decode
+    attention and one of step prefill are captured once and replayed three times, with
+    eager work and synchronisations of the program in between; every replay reproduces the
+    eager results bit for bit after the outputs were overwritten."""
+    from workload import make_prefill_queries_host
+    cfg = CONFIGS["c3_pruned"]
+    tree = make_tree(cfg)
+    layers = 3
+    kd, vd, qd = make_values_device(cfg, tree, "cuda:0", layers=layers)
+    qs = to_device(make_prefill_queries_host(cfg, tree))
+    L, hq, d = tree.n_leaves, cfg.n_q_heads, cfg.head_dim
+    with make_ctx(cfg) as ctx:
+        st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        ps = ctx.plan_prefill(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        out = torch.zeros((layers, L, hq, d), device="cuda:0")
+        lse = torch.zeros((layers, L, hq), device="cuda:0")
+        outp = torch.zeros((ps.n_q_rows, hq, d), device="cuda:0")
+        lsep = torch.zeros((ps.n_q_rows, hq), device="cuda:0")
+        ws = torch.empty(max(st.workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+
+        def step(stream):
+            for l in range(layers):
+                ctx.decode(kd[l], vd[l], tree.pool_tokens, qd[l], out[l], lse[l], ws, ws.numel(),
+                           stream)
+            ctx.prefill(kd[0], vd[0], tree.pool_tokens, qs, outp, lsep, stream)
+
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            step(s.cuda_stream)
+        torch.cuda.synchronize()
+        ref = [t.clone() for t in (out, lse, outp, lsep)]
+        print("case graph capture", flush=True)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            step(s.cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for t in (out, lse, outp, lsep):
+                t.fill_(float("nan"))                 # eager work between the replays
+            ws.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for t, r in zip((out, lse, outp, lsep), ref):
+                assert torch.equal(t, r), "replay %d differs from the eager run" % rep
+            # an eager call between replays still works on the same context and plan
+            with torch.cuda.stream(s):
+                ctx.decode(kd[0], vd[0], tree.pool_tokens, qd[0], out[0], lse[0], ws, ws.numel(),
+                           s.cuda_stream)
+            torch.cuda.synchronize()
+            assert torch.equal(out[0], ref[0][0])
+        del g
