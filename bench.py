@@ -287,6 +287,29 @@ def main():
             (el8 * 1e6, variants["fp8_kv"]["speedup_vs_bf16_pools"], us8,
              variants["fp8_kv"]["roofline"]["achieved"],
              variants["fp8_kv"]["roofline"]["frac"] * 100))
+        if args.prefill_layers > 0:
+            # step prefill over the same E4M3 pools (matrix-core bound: the bytes matter little)
+            pst8 = ctx.plan_prefill(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+            qp8 = torch.randn((pst8.n_q_rows, hq, d), device=dev).to(torch.bfloat16)
+            op8 = torch.empty((pst8.n_q_rows, hq, d), dtype=torch.float32, device=dev)
+            lp8 = torch.empty((pst8.n_q_rows, hq), dtype=torch.float32, device=dev)
+            ctx.prefill(k8[0], v8[0], tree.pool_tokens, qp8, op8, lp8, stream.cuda_stream)
+            n_l8 = min(args.prefill_layers, 2)
+            e8 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            e8[0].record(stream)
+            for i in range(n_l8):
+                ctx.prefill(k8[(i + 1) % n8], v8[(i + 1) % n8], tree.pool_tokens, qp8, op8, lp8,
+                            stream.cuda_stream)
+            e8[1].record(stream)
+            torch.cuda.synchronize()
+            ms8 = e8[0].elapsed_time(e8[1]) / n_l8
+            variants["fp8_kv"]["prefill"] = {
+                "layers_timed": n_l8, "ms_per_layer": round(ms8, 3),
+                "tflops": round(pst8.flops / (ms8 * 1e-3) / 1e12, 1),
+                "frac_of_mfma_peak": round(pst8.flops / (ms8 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}
+            log("E4M3 pools, step prefill: %.2f ms per layer = %.0f TFLOP/s" %
+                (ms8, variants["fp8_kv"]["prefill"]["tflops"]))
+            del qp8, op8, lp8
         if fp8_check is None:
             del k8, v8, q8
         del ws8, out8, lse8

@@ -219,8 +219,8 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
  *                    bf16.  Only for bf16 contexts with head_dim 128 (ETS_ERR_UNSUPPORTED
  *                    otherwise) and with the "mfma" option on (else ets_tree_decode_attn
  *                    returns ETS_ERR_UNSUPPORTED).  ets_kv_append then copies 1-byte
- *                    elements (k_new, v_new hold codes); step prefill is not available
- *                    (ets_plan_prefill returns ETS_ERR_UNSUPPORTED).
+ *                    elements (k_new, v_new hold codes); step prefill reads such pools
+ *                    as well (its q stays bf16, its output fp32).
  * The scales are ignored for ETS_KV_NATIVE.  The call drops the current plans: run
  * ets_plan again (byte statistics and work-item sizes follow the element size). */
 typedef enum { ETS_KV_NATIVE = 0, ETS_KV_FP8_E4M3 = 1 } ets_kv_format;
@@ -311,7 +311,8 @@ ets_status ets_prefill_q_ptr(const ets_ctx* ctx, int64_t* q_ptr);
 ets_status ets_prefill_cover(const ets_ctx* ctx, int32_t leaf, int32_t tok, int64_t* rows,
                              int64_t cap, int64_t* n_rows);
 /* One layer of step-prefill attention.
- *   k_pool, v_pool, pool_tokens   as in ets_tree_decode_attn
+ *   k_pool, v_pool, pool_tokens   as in ets_tree_decode_attn (E4M3 codes after
+ *         ets_set_kv_format, which has to precede ets_plan_prefill)
  *   q     DEVICE, [n_q_rows][n_q_heads][head_dim] bf16, 16-byte aligned
  *   out   DEVICE, [n_q_rows][n_q_heads][head_dim] float, 16-byte aligned
  *   lse   DEVICE, [n_q_rows][n_q_heads] float

@@ -288,6 +288,24 @@ def tree_prefill_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q
     return out, lse
 
 
+def tree_prefill_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
+                            v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
+    """Step-prefill attention over pools stored as E4M3 codes with one scale each: the
+    definition of tree_prefill_attn on K = k_scale * value(k_codes), V = v_scale *
+    value(v_codes), evaluated like tree_decode_attn_fp8kv (scores are linear in K, the
+    output in V)."""
+    from .fp8 import decode_e4m3
+    q = np.asarray(q)
+    if q.dtype == np.uint16:
+        q = (q.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    base = float(sm_scale) if sm_scale > 0 else 1.0 / float(np.sqrt(np.float64(head_dim)))
+    out, lse = tree_prefill_attn(parent, tok_offset, n_tokens, leaf_node, decode_e4m3(k_codes),
+                                 decode_e4m3(v_codes), np.ascontiguousarray(q, dtype=np.float32),
+                                 n_kv_heads, n_q_heads, head_dim, sm_scale=base * float(k_scale),
+                                 rows=rows)
+    return out * float(v_scale), lse
+
+
 def visible_rows(parent, tok_offset, n_tokens, node, own_rows=None):
     """Pool rows a query on `node` sees, in path order: all rows of the strict ancestors,
     then the first `own_rows` rows of the node (None: all of them)."""

@@ -565,8 +565,8 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
 ets_status ets_plan_prefill(ets_ctx* ctx, const ets_tree* tree) {
     if (!ctx || !tree) return ETS_ERR_INVALID_ARG;
     if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
-    if (ctx->kv_format != ETS_KV_NATIVE) return ETS_ERR_UNSUPPORTED;
-    ets_status s = build_prefill_plan(ctx->shape, *tree, ctx->prefill);
+    ets_status s = build_prefill_plan(ctx->shape, *tree, ctx->prefill,
+                                      ctx->kv_format == ETS_KV_FP8_E4M3 ? 1 : 2);
     if (s != ETS_OK) return s;
     if (ctx->device >= 0) {
         s = upload_prefill_plan(ctx);
@@ -631,11 +631,17 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
     // grid: x = kv head, y = item, at most 65535 items per launch
     for (int64_t y0 = 0; y0 < st.n_items; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, st.n_items - y0);
-        hipLaunchKernelGGL(prefill_attn_kernel, dim3((unsigned)ctx->shape.n_kv_heads, ny), dim3(512),
-                           0, stream, static_cast<const bf16_t*>(k_pool),
-                           static_cast<const bf16_t*>(v_pool), pool_tokens,
-                           static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items, (int)y0,
-                           g_shift, ctx->scale * 1.4426950408889634f, out, lse);
+        if (ctx->kv_format == ETS_KV_FP8_E4M3)
+            hipLaunchKernelGGL(prefill_attn_kernel<true>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
+                               dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
+                               static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
+                               (int)y0, g_shift, ctx->scale * ctx->k_scale * 1.4426950408889634f,
+                               ctx->v_scale, out, lse);
+        else
+            hipLaunchKernelGGL(prefill_attn_kernel<false>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
+                               dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
+                               static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
+                               (int)y0, g_shift, ctx->scale * 1.4426950408889634f, 1.0f, out, lse);
     }
     ctx->last_stream = stream;
     ctx->stream_used = true;

@@ -166,11 +166,15 @@ __device__ __forceinline__ float prefill_unit(const u32x4_t* __restrict__ ks_nex
     return mx;
 }
 
+// FP8: the pools hold E4M3 codes (128-byte rows, 8 bytes per lane and load); the codes are
+// widened while the tile is staged (K to bf16, V straight to the fp16 fragments), the K
+// scale is part of scale_log2e and the V scale (out_scale) multiplies the normalised rows.
+template <bool FP8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attn_kernel(
-    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t pool_tokens,
+    const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ runs,
     const PrefillItem* __restrict__ items, int item_base, int g_shift, float scale_log2e,
-    float* __restrict__ out, float* __restrict__ lse) {
+    float out_scale, float* __restrict__ out, float* __restrict__ lse) {
     constexpr int D = 128;
     constexpr int KROW = kTreeAttnKRow;
     constexpr int KS_UNITS = 64 * KROW;    // K tile: 64 rows of 272 bytes
@@ -202,37 +206,49 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     // the wave's 16 rows of K (rows b + 4 i) or of V (rows 4 b + i) of two tiles in flight:
     // loads are issued three tiles ahead of their use, and a register set is busy from
     // the issue until its tile is staged, so two sets alternate
-    u32x4_t raw0[4], raw1[4];
-    constexpr uint32_t stride_b = D * 2;
+    using raw_t = std::conditional_t<FP8, u32x2_t, u32x4_t>;
+    raw_t raw0[4], raw1[4];
+    constexpr uint32_t stride_b = FP8 ? D : D * 2;
     const int64_t plane = (int64_t)h * pool_tokens;
-    const bf16_t* pool = loads_v ? v_pool : k_pool;
-    const uint32_t lane_off = (uint32_t)(16 * hw + (loads_v ? 4 * b : b)) * stride_b + a * 16;
+    const void* pool = loads_v ? v_pool : k_pool;
+    const uint32_t lane_off =
+        (uint32_t)(16 * hw + (loads_v ? 4 * b : b)) * stride_b + a * (FP8 ? 8 : 16);
     const uint32_t load_step = (loads_v ? 1u : 4u) * stride_b;
     // a run's rows through a descriptor that covers exactly the run: rows past the end of
     // a short run read as zero (and are masked); an empty run (past the end of an odd
     // list) is staged as zeros
-    auto issue_loads = [&](const Run& sd, u32x4_t (&raw)[4]) {
+    auto issue_loads = [&](const Run& sd, raw_t (&raw)[4]) {
         // always four loads (an empty run's descriptor covers nothing: every lane reads
         // zero without a memory access), so that the number of loads in flight is known
         // at every wait
-        const int64_t base = (plane + sd.tok) * (int64_t)D * 2;
+        const int64_t base = (plane + sd.tok) * (int64_t)stride_b;
         char* pb = const_cast<char*>(reinterpret_cast<const char*>(pool)) + base;
         const int bytes = sd.n * (int)stride_b;
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(pb, 0, bytes, 0x00020000);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            raw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                                     rs, lane_off + (uint32_t)i * load_step, 0, 0));
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (FP8)
+                raw[i] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(
+                                                         rs, lane_off + (uint32_t)i * load_step, 0, 0));
+            else
+                raw[i] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                         rs, lane_off + (uint32_t)i * load_step, 0, 0));
+        }
     };
     // K: row-major rows of 272 bytes.  V: lane (a, b) holds run rows 16 hw + 4 b + i
     // (i = 0..3) at d = 8 a + x (x = 0..7); the four rows at one d are half (b >> 1) of
     // the 16-byte A fragment of lane (d % 32, b & 1) in d block d / 32 of half hw.
-    auto stage = [&](int buf, const u32x4_t (&raw)[4]) {
+    auto stage = [&](int buf, const raw_t (&raw)[4]) {
         u32x4_t* ks = smem + buf * BUF_UNITS;
         u32x2_t* vs2 = reinterpret_cast<u32x2_t*>(ks + KS_UNITS);
         if (!loads_v) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = raw[i];
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (FP8)
+                    ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = e4m3x8_to_bf16x8(raw[i]);
+                else
+                    ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = raw[i];
+            }
         } else {
             const int frag = (sw * 2 + hw) * 4 + (a >> 2);    // [run][half][d block]
             const int dst_lane = 32 * (b & 1) + 8 * (a & 3);  // + x
@@ -243,14 +259,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 u32x2_t te, to;
-                te[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(raw[0][j]),
-                                                                                bf16_lo(raw[1][j])));
-                te[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(raw[2][j]),
-                                                                                bf16_lo(raw[3][j])));
-                to[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_hi(raw[0][j]),
-                                                                                bf16_hi(raw[1][j])));
-                to[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_hi(raw[2][j]),
-                                                                                bf16_hi(raw[3][j])));
+                if constexpr (FP8) {
+                    // elements 2 j and 2 j + 1 of the four rows as floats (exact), then
+                    // fp16 pairs across rows
+                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                    f32x2_t f[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        f[i] = (j & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[i][j >> 1], true)
+                                       : __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[i][j >> 1], false);
+                    te[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[0][0], f[1][0]));
+                    te[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[2][0], f[3][0]));
+                    to[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[0][1], f[1][1]));
+                    to[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[2][1], f[3][1]));
+                } else {
+                    te[0] = __builtin_bit_cast(
+                        uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(raw[0][j]), bf16_lo(raw[1][j])));
+                    te[1] = __builtin_bit_cast(
+                        uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(raw[2][j]), bf16_lo(raw[3][j])));
+                    to[0] = __builtin_bit_cast(
+                        uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_hi(raw[0][j]), bf16_hi(raw[1][j])));
+                    to[1] = __builtin_bit_cast(
+                        uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_hi(raw[2][j]), bf16_hi(raw[3][j])));
+                }
                 dst[(slot0 ^ (2 * j)) * 2] = te;      // x = 2 j
                 dst[(slot0 ^ (2 * j + 1)) * 2] = to;  // x = 2 j + 1
             }
@@ -327,7 +358,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 
     int cur = 0, nxt = 1;  // tile % 3, (tile + 1) % 3
     // one tile; `raw` holds the rows of tile + 1 and takes those of tile + 3
-    auto do_tile = [&](int tile, u32x4_t (&raw)[4]) {
+    auto do_tile = [&](int tile, raw_t (&raw)[4]) {
         const u32x4_t* ks = smem + cur * BUF_UNITS;
         const u32x4_t* vs = ks + KS_UNITS;
         const u32x4_t* ks_next = smem + nxt * BUF_UNITS;
@@ -380,7 +411,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
     float l = lsum;
     l += __shfl_xor(l, 32, 64);
-    const float inv = 1.0f / l;
+    float inv = 1.0f / l;
+    if constexpr (FP8) inv *= out_scale;
     if (g == 0 && (r_lane >> g_shift) < it.n_tok)
         lse[(it.q_row0 + tq_lane) * n_q_heads + h * G + (r_lane & (G - 1))] =
             (m * scale_log2e + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;

@@ -27,7 +27,8 @@ ets_status check(const ets_tree& t) {
     return ETS_OK;
 }
 
-ets_status build(const ets_shape& shape, const ets_tree& tree, PrefillPlan& p) {
+ets_status build(const ets_shape& shape, const ets_tree& tree, PrefillPlan& p,
+                 int64_t kv_elem_bytes) {
     const int32_t N = tree.n_nodes, L = tree.n_leaves;
     const int32_t G = shape.n_q_heads / shape.n_kv_heads;
     const int32_t tq = kPrefillRowsPerItem / G;  // query tokens per item
@@ -162,7 +163,7 @@ ets_status build(const ets_shape& shape, const ets_tree& tree, PrefillPlan& p) {
         if (p.n_tokens[i] > 0)
             st.min_pool_tokens = std::max(st.min_pool_tokens, p.tok_offset[i] + p.n_tokens[i]);
     }
-    const int64_t tok_bytes = 2 * (int64_t)shape.n_kv_heads * shape.head_dim * 2;
+    const int64_t tok_bytes = 2 * (int64_t)shape.n_kv_heads * shape.head_dim * kv_elem_bytes;
     st.unique_kv_bytes = st.unique_tokens * tok_bytes;
     st.streamed_kv_bytes = st.streamed_tokens * tok_bytes;
     // two contractions of head_dim per (query row, visible key row), 2 flops per multiply-add
@@ -173,12 +174,13 @@ ets_status build(const ets_shape& shape, const ets_tree& tree, PrefillPlan& p) {
 
 }  // namespace
 
-ets_status build_prefill_plan(const ets_shape& shape, const ets_tree& tree, PrefillPlan& plan) {
+ets_status build_prefill_plan(const ets_shape& shape, const ets_tree& tree, PrefillPlan& plan,
+                              int64_t kv_elem_bytes) {
     plan.valid = false;
     const ets_status s = check(tree);
     if (s != ETS_OK) return s;
     try {
-        return build(shape, tree, plan);
+        return build(shape, tree, plan, kv_elem_bytes);
     } catch (const std::bad_alloc&) {
         plan.valid = false;
         return ETS_ERR_NOMEM;

@@ -44,7 +44,9 @@ struct PrefillPlan {
 
 // Builds `plan`; ETS_OK, ETS_ERR_BAD_TREE, ETS_ERR_BAD_LEAF, ETS_ERR_INVALID_ARG,
 // ETS_ERR_UNSUPPORTED (more than 2^31 - 1 runs or query rows per node) or ETS_ERR_NOMEM.
-ets_status build_prefill_plan(const ets_shape& shape, const ets_tree& tree, PrefillPlan& plan);
+// kv_elem_bytes: bytes per pool element for the byte statistics (2 = bf16, 1 = E4M3 codes)
+ets_status build_prefill_plan(const ets_shape& shape, const ets_tree& tree, PrefillPlan& plan,
+                              int64_t kv_elem_bytes = 2);
 
 // Pool rows that query token `tok` of leaf query `leaf` sees according to the work
 // items (their run lists and the visibility rule above), in the order they are read.

@@ -9,8 +9,8 @@ import paper_2502_13575_amd as ets
 from workload import (CONFIGS, TreeConfig, make_tree, make_values_fp8_device, make_values_fp8_host,
                       make_values_host, random_tree, with_growth_room)
 
-from _gpu_util import (compare, make_ctx, oracle_full, pool_to_device, pool_to_host, to_device,
-                       to_host_bits)
+from _gpu_util import (compare, gpu_prefill, make_ctx, oracle_full, pool_to_device, pool_to_host,
+                       to_device, to_host_bits)
 
 pytestmark = pytest.mark.gpu
 
@@ -180,3 +180,61 @@ def test_fp8kv_with_bf16_output():
     err = np.abs(o16.float().cpu().numpy().astype(np.float64) - oo)
     assert np.all(err <= 2e-3 + 2.0 ** -8 * np.abs(oo)), err.max()
     assert np.abs(lse.cpu().numpy() - ol).max() <= 2e-3
+
+
+def oracle_prefill_fp8(cfg, tree, kc, vc, q, ks, vs, rows=None):
+    return oracle.tree_prefill_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens,
+                                          tree.leaf_node, kc, vc, ks, vs, q, cfg.n_kv_heads,
+                                          cfg.n_q_heads, cfg.head_dim, rows=rows)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_fp8kv_prefill_fuzz_irregular_forests(seed):
+    """Step prefill over E4M3 pools on irregular forests (ragged runs, empty nodes, duplicate
+    and interior leaf queries), every row against the oracle."""
+    from workload import make_prefill_queries_host
+    hkv, hq = [(2, 8), (1, 8), (4, 4), (2, 4), (1, 2), (2, 16)][seed]
+    cfg = TreeConfig("pfuzz8", hkv, hq, 128, "bf16", 0, 0, 0, 0, 0, None, seed=800 + seed)
+    tree = random_tree(500 + seed, n_nodes=40, n_leaves=9, max_tokens=[70, 150, 40][seed % 3])
+    ks, vs = [(KS, VS), (1.0, 1.0), (0.5, 3.0)][seed % 3]
+    kc, vc, _ = make_values_fp8_host(cfg, tree, ks, vs)
+    q = make_prefill_queries_host(cfg, tree)
+    print("case fp8 prefill fuzz", seed, flush=True)
+    with make_ctx(cfg) as ctx:
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, ks, vs)
+        out, lse, st = gpu_prefill(ctx, tree, pool_to_device(kc), pool_to_device(vc), to_device(q))
+    assert st.unique_kv_bytes == st.unique_tokens * 2 * hkv * 128
+    if st.n_q_rows == 0:
+        return
+    oo, ol = oracle_prefill_fp8(cfg, tree, kc, vc, q, ks, vs)
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "fp8 prefill fuzz%d" % seed)
+
+
+def test_fp8kv_prefill_c3_sampled_and_decode_on_one_context():
+    """One context with E4M3 pools serves decode attention and step prefill of the same tree."""
+    from workload import make_prefill_queries_host
+    cfg = CONFIGS["c3_pruned"]
+    tree = make_tree(cfg)
+    kc, vc, q = make_values_fp8_host(cfg, tree, KS, VS)
+    qs = make_prefill_queries_host(cfg, tree)
+    kd, vd = pool_to_device(kc), pool_to_device(vc)
+    with make_ctx(cfg) as ctx:
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, KS, VS)
+        outp, lsep, _ = gpu_prefill(ctx, tree, kd, vd, to_device(qs))
+        out, lse, _ = run(ctx, tree, kd, vd, to_device(q))
+    r = np.random.default_rng(31)
+    n = 96
+    sl = r.integers(0, tree.n_leaves, size=n).astype(np.int32)
+    lens = tree.n_tokens[tree.leaf_node[sl]]
+    stok = (r.random(n) * lens).astype(np.int32)
+    stok[:6] = 0
+    stok[6:12] = lens[6:12] - 1
+    sh = r.integers(0, cfg.n_q_heads, size=n).astype(np.int32)
+    rows = oracle.prefill_q_ptr(tree.n_tokens, tree.leaf_node)[sl] + stok
+    oo, ol = oracle_prefill_fp8(cfg, tree, kc, vc, qs, KS, VS, rows=(sl, stok, sh))
+    compare(outp.cpu().numpy()[rows, sh], lsep.cpu().numpy()[rows, sh], oo, ol, "bf16",
+            "fp8 prefill c3")
+    do, dl = oracle_fp8(cfg, tree, kc, vc, q)
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            do.reshape(-1, 128), dl.reshape(-1), "bf16", "fp8 decode c3")

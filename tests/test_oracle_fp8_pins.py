@@ -140,3 +140,43 @@ def test_quantiser_of_the_input_generator_rounds_to_nearest_code():
     best = np.abs(y[:, None] - fin[None, :]).min(axis=1)
     assert np.all(np.isfinite(val))
     assert np.all(np.abs(val - y) <= best * (1 + 1e-12) + 0.0)
+
+
+def test_fp8kv_prefill_against_dense_masked_softmax_and_the_bf16_oracle():
+    """Step prefill over E4M3 pools: every query token against a dense fp64 softmax over the
+    rows it sees (ancestors in full, own node up to itself) on explicitly dequantised pools;
+    with unit scales, bitwise the bf16 prefill oracle on the same values."""
+    from workload import make_prefill_queries_host
+    cfg = CONFIGS["c2_w16"]
+    hkv, hq, d = 2, 4, 128
+    tree = random_tree(77, 14, 5, 9)
+    ks, vs = 0.31, 1.7
+    kc, vc, _ = make_values_fp8_host(cfg, tree, ks, vs, seed=5)
+    kc, vc = np.ascontiguousarray(kc[:, :hkv]), np.ascontiguousarray(vc[:, :hkv])
+    nrows = int(tree.n_tokens[tree.leaf_node].sum())
+    q = to_bf16_bits(np.random.default_rng(9).standard_normal((nrows, hq, d)).astype(np.float32))
+    out, lse = oracle.tree_prefill_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens,
+                                              tree.leaf_node, kc, vc, ks, vs, q, hkv, hq, d)
+    K = E4M3_TABLE[kc] * ks
+    V = E4M3_TABLE[vc] * vs
+    Q = bf16_bits_to_f32(q).astype(np.float64)
+    sm = 1.0 / math.sqrt(d)
+    r = 0
+    for l in range(tree.n_leaves):
+        node = tree.leaf_node[l]
+        for i in range(tree.n_tokens[node]):
+            rows = oracle.visible_rows(tree.parent, tree.tok_offset, tree.n_tokens, node, i + 1)
+            for j in range(hq):
+                s = sm * (K[rows, j // (hq // hkv), :] @ Q[r, j])
+                w = np.exp(s - s.max())
+                assert abs(lse[r, j] - (s.max() + np.log(w.sum()))) < 1e-12
+                assert np.allclose(out[r, j], (w / w.sum()) @ V[rows, j // (hq // hkv), :],
+                                   rtol=1e-10, atol=1e-12)
+            r += 1
+    assert r == nrows
+    a = oracle.tree_prefill_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                       kc, vc, 1.0, 1.0, q, hkv, hq, d)
+    b = oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                 to_bf16_bits(decode_e4m3(kc)), to_bf16_bits(decode_e4m3(vc)), q,
+                                 hkv, hq, d)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])

@@ -272,8 +272,8 @@ def test_advance_and_append_error_paths():
 
 def test_kv_format_host_logic():
     """E4M3 pools: accepted only where the matrix-core kernel runs, the plans are dropped,
-    byte statistics follow the 1-byte elements, the indexing does not change, and step
-    prefill is refused."""
+    byte statistics follow the 1-byte elements (of the prefill plan too), the indexing does
+    not change."""
     cfg = CONFIGS["c3_pruned"]
     t = make_tree(cfg)
     with _ctx(cfg) as ctx:
@@ -289,9 +289,7 @@ def test_kv_format_host_logic():
         with pytest.raises(ets.EtsError) as e:
             ctx.stats()
         assert e.value.status == 6                                     # plan dropped
-        with pytest.raises(ets.EtsError) as e:
-            ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
-        assert e.value.status == 4
+        pf1 = ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
         st1 = _check_plan_against_oracle(ctx, t, ets.ETS_PLAN_TREE,
                                          list(range(0, t.n_leaves, 4)), esz=1)
         assert st1.unique_tokens == st2.unique_tokens
@@ -301,7 +299,10 @@ def test_kv_format_host_logic():
         ctx.set_kv_format(ets.ETS_KV_NATIVE)
         st3 = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
         assert st3.unique_kv_bytes == st2.unique_kv_bytes
-        ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        pf2 = ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert 2 * pf1.unique_kv_bytes == pf2.unique_kv_bytes
+        assert 2 * pf1.streamed_kv_bytes == pf2.streamed_kv_bytes
+        assert (pf1.n_items, pf1.n_runs, pf1.flops) == (pf2.n_items, pf2.n_runs, pf2.flops)
     for shape in [(2, 4, 64, ets.ETS_BF16), (2, 4, 128, ets.ETS_F32)]:
         with _ctx(shape) as ctx:
             with pytest.raises(ets.EtsError) as e:
