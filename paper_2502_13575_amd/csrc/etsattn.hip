@@ -91,9 +91,13 @@ ets_status upload_plan(ets_ctx* c) {
     const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
     const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
-    // the kernel reads up to 16 entries past an item's own with scalar loads: both
-    // per-entry tables get 16 zero entries at the end
-    const size_t b_ent = align_up((p.ent_order.size() + 16) * sizeof(int32_t), 256);
+    // Every wave of a workgroup looks up the entries of "its" 16 query rows, also a wave
+    // whose row block lies past the item's last row (it computes nothing, but it fetches
+    // the query rows those entries name): with one query head per kv head that is up to
+    // kTreeAttnRowsPerItem entries from the item's first one, whatever the item's own
+    // count.  Both per-entry tables end in that many zero entries (leaf query 0, slot 0).
+    const size_t b_ent =
+        align_up((p.ent_order.size() + kTreeAttnRowsPerItem) * sizeof(int32_t), 256);
     const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
     const size_t b_adv = align_up(p.adv.size() * sizeof(AdvEntry), 256);
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);

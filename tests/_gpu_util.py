@@ -75,7 +75,9 @@ def compare(out_g, lse_g, out_o, lse_o, dtype, what=""):
     max_abs_l = float(err_l.max()) if err_l.size else 0.0
     row_scale = np.maximum(np.abs(out_o).max(axis=-1), 1e-30)
     rel_o = float((err_o.max(axis=-1) / row_scale)[fin].max()) if fin.any() else 0.0
-    rel_l = float((err_l / np.maximum(np.abs(lse_o[fin]), 1e-30)).max()) if fin.any() else 0.0
+    # lse is a logarithm and passes through zero (a sum of weights near one): its error is
+    # measured relative to max(|lse|, 1), i.e. absolutely where |lse| is small
+    rel_l = float((err_l / np.maximum(np.abs(lse_o[fin]), 1.0)).max()) if fin.any() else 0.0
     msg = "%s: out max-abs %.3g row-rel %.3g; lse max-abs %.3g rel %.3g" % (
         what, max_abs_o, rel_o, max_abs_l, rel_l)
     assert max_abs_o <= tol["abs"] and max_abs_l <= tol["abs"], msg

@@ -399,3 +399,43 @@ def test_decode_and_prefill_under_graph_capture():
             torch.cuda.synchronize()
             assert torch.equal(out[0], ref[0][0])
         del g
+
+
+def test_row_blocks_past_an_items_last_row():
+    """Regression: an item with 17..48 query rows and one query head per kv head leaves
+    whole 16-row blocks of its workgroup without rows; their waves still look up entries
+    (up to 63 past the item's first) and fetch the query rows those name, so the entry
+    tables must end in enough padding.  The forest below (the case that exposed it: 47
+    leaf entries, an item with 24 of them starting at entry 21) is checked in full."""
+    seed = 2587
+    r = np.random.default_rng(seed)
+    tree = random_tree(seed, n_nodes=int(r.integers(2, 160)), n_leaves=int(r.integers(1, 100)),
+                       max_tokens=int(r.choice([5, 20, 40, 90, 200, 500])),
+                       p_root=float(r.choice([0.02, 0.1, 0.3])),
+                       p_empty=float(r.choice([0.0, 0.15, 0.4])))
+    options = {"stream_chunk": int(r.choice([0, 32, 64])), "cascade_chunk": int(r.choice([0, 32, 96])),
+               "cascade_rows": int(r.choice([64, 16, 32])),
+               "wave_items": int(r.choice([512, 0, 48, 100000])),
+               "cascade_min_leaves": int(r.choice([2, 2, 0, 3]))}
+    assert tree.n_leaves == 47
+    cfg = TreeConfig("pad", 2, 2, 128, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
+    k, v, q = make_values_host(cfg, tree)
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    print("case entry padding", options, flush=True)
+    with make_ctx(cfg, options) as ctx:
+        out, lse, _ = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "entry padding")
+    # one head per kv head, 17..48 leaves under one node, few entries in all
+    for n_leaves in (17, 24, 33, 48):
+        parent = np.array([-1] + [0] * n_leaves, np.int32)
+        n_tokens = np.array([70] + [3] * n_leaves, np.int32)
+        tok_offset = (np.cumsum(n_tokens) - n_tokens).astype(np.int64)
+        t2 = type(tree)(parent, tok_offset, n_tokens, np.arange(1, n_leaves + 1, dtype=np.int32),
+                        int(n_tokens.sum()))
+        k, v, q = make_values_host(cfg, t2)
+        oo, ol = oracle_full(cfg, t2, k, v, q)
+        with make_ctx(cfg) as ctx:
+            out, lse, _ = gpu_attn(ctx, t2, pool_to_device(k), pool_to_device(v), to_device(q))
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "entry padding %d" % n_leaves)
