@@ -447,8 +447,10 @@ ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_
     const int n = (int)p.adv_node.size();
     if (n == 0) return ETS_OK;
     if (!k_pool || !v_pool || !k_new || !v_new) return ETS_ERR_INVALID_ARG;
-    // every node's next row has to exist in the pool
-    if (pool_tokens < p.stats.min_pool_tokens + 1) return ETS_ERR_INVALID_ARG;
+    // every growing node's next row has to exist in the pool
+    int64_t last_row = -1;
+    for (const int64_t r0 : p.adv_row0) last_row = std::max(last_row, r0 + p.advances);
+    if (last_row >= pool_tokens) return ETS_ERR_INVALID_ARG;
     const int64_t esz =
         ctx->kv_format == ETS_KV_FP8_E4M3 ? 1 : ctx->shape.dtype == ETS_F32 ? 4 : 2;
     const int head_bytes = (int)(ctx->shape.head_dim * esz);

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import paper_2502_13575_amd as ets
-from workload import (CONFIGS, TreeConfig, make_tree, make_values_device, make_values_host,
+from workload import (CONFIGS, Tree, TreeConfig, make_tree, make_values_device, make_values_host,
                       random_tree)
 
 from _gpu_util import (compare, gpu_attn, make_ctx, oracle_full, oracle_rows, pool_to_device,
@@ -439,3 +439,49 @@ def test_row_blocks_past_an_items_last_row():
             out, lse, _ = gpu_attn(ctx, t2, pool_to_device(k), pool_to_device(v), to_device(q))
         compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
                 oo.reshape(-1, 128), ol.reshape(-1), "bf16", "entry padding %d" % n_leaves)
+
+
+def test_kv_append_needs_room_only_behind_growing_nodes():
+    """The pool has to hold the next row of every node that grows, nothing more: a tree whose
+    last pool rows belong to an inner node appends fine without a spare row at the pool's
+    end, and the appended rows land where the oracle puts them."""
+    cfg = TreeConfig("room", 2, 8, 128, "bf16", 0, 0, 0, 0, 0, None, seed=77)
+    # pool order: leaf node 1 (5 rows + 2 spare), leaf node 2 (4 rows + 2 spare), root (9 rows, last)
+    parent = np.array([-1, 0, 0], np.int32)
+    n_tokens = np.array([9, 5, 4], np.int32)
+    tok_offset = np.array([13, 0, 7], np.int64)
+    tree = Tree(parent, tok_offset, n_tokens, np.array([1, 2], np.int32), 22)
+    k, v, q = make_values_host(cfg, tree)
+    kd, vd, qd = pool_to_device(k), pool_to_device(v), to_device(q)
+    from workload import make_new_tokens_host
+    nt = n_tokens.copy()
+    with make_ctx(cfg) as ctx:
+        st = ctx.plan(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node)
+        assert st.min_pool_tokens == 22
+        for step in range(2):
+            kn, vn = make_new_tokens_host(cfg, tree, step)
+            nt = oracle.append_kv(tree.tok_offset, nt, tree.leaf_node, k, v, kn, vn)
+            ctx.kv_append(kd, vd, tree.pool_tokens, to_device(kn), to_device(vn))
+            ctx.plan_advance()
+        # the spare rows are used up: node 2's next row would be the root's first
+        # (not detected: overlap is the caller's business), node 1's next row 7 is node 2's
+        out = torch.full((2, 8, 128), float("nan"), device="cuda:0")
+        lse = torch.full((2, 8), float("nan"), device="cuda:0")
+        ws = torch.empty(max(ctx.stats().workspace_bytes, 16), dtype=torch.uint8, device="cuda:0")
+        ctx.decode(kd, vd, tree.pool_tokens, qd, out, lse, ws, ws.numel())
+        torch.cuda.synchronize()
+    assert np.array_equal(pool_to_host(kd), k) and np.array_equal(pool_to_host(vd), v)
+    grown = Tree(parent, tok_offset, nt, tree.leaf_node, 22)
+    oo, ol = oracle_full(cfg, grown, k, v, q)
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "append room")
+    # a growing node at the very end of the pool without a spare row is still refused
+    t2 = Tree(np.array([-1, 0], np.int32), np.array([0, 9], np.int64), np.array([9, 4], np.int32),
+              np.array([1], np.int32), 13)
+    k2, v2, q2 = make_values_host(cfg, t2)
+    with make_ctx(cfg) as ctx:
+        ctx.plan(t2.parent, t2.tok_offset, t2.n_tokens, t2.leaf_node)
+        kn, vn = make_new_tokens_host(cfg, t2, 0)
+        with pytest.raises(ets.EtsError) as e:
+            ctx.kv_append(pool_to_device(k2), pool_to_device(v2), 13, to_device(kn), to_device(vn))
+        assert e.value.status == 1
