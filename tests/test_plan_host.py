@@ -208,8 +208,8 @@ def _check_cover(ctx, t, n_tokens):
     st = ctx.stats()
     ost = oracle.tree_stats(grown.parent, grown.n_tokens, grown.leaf_node)
     assert st.unique_tokens == ost["unique_tokens"] and st.flat_tokens == ost["flat_tokens"]
-    assert st.min_pool_tokens == max(int((grown.tok_offset + grown.n_tokens)[
-        ost["leaf_count"] > 0].max(initial=0)), 0)
+    holds = (ost["leaf_count"] > 0) & (grown.n_tokens > 0)       # live nodes that own rows
+    assert st.min_pool_tokens == max(int((grown.tok_offset + grown.n_tokens)[holds].max(initial=0)), 0)
     optr, onodes = oracle.paths(grown.parent, grown.leaf_node)
     total = 0
     for l in range(grown.n_leaves):
