@@ -238,3 +238,49 @@ def test_fp8kv_prefill_c3_sampled_and_decode_on_one_context():
     do, dl = oracle_fp8(cfg, tree, kc, vc, q)
     compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
             do.reshape(-1, 128), dl.reshape(-1), "bf16", "fp8 decode c3")
+
+
+def test_wide_random_sweep():
+    """Two hundred random forests (1..160 nodes, 1..100 leaf queries, every group size,
+    random planner knobs, both pool formats; every third one also step prefill), every
+    output row against the oracle.  Cheap on the GPU, and wide enough to hit layouts the
+    hand-made cases miss (it found the entry-table padding and the append room check)."""
+    from workload import make_prefill_queries_host
+    shapes = [(2, 8), (1, 1), (2, 16), (4, 8), (1, 2), (8, 32), (3, 12), (2, 2), (1, 8), (4, 4)]
+    for seed in range(5000, 5200):
+        r = np.random.default_rng(seed)
+        hkv, hq = shapes[seed % len(shapes)]
+        cfg = TreeConfig("sweep", hkv, hq, 128, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
+        tree = random_tree(seed, n_nodes=int(r.integers(2, 160)), n_leaves=int(r.integers(1, 100)),
+                           max_tokens=int(r.choice([5, 20, 40, 90, 200, 500])),
+                           p_root=float(r.choice([0.02, 0.1, 0.3])),
+                           p_empty=float(r.choice([0.0, 0.15, 0.4])))
+        options = {"stream_chunk": int(r.choice([0, 32, 64])),
+                   "cascade_chunk": int(r.choice([0, 32, 96])),
+                   "cascade_rows": int(r.choice([64, 16, 32])),
+                   "wave_items": int(r.choice([512, 0, 48, 100000])),
+                   "cascade_min_leaves": int(r.choice([2, 2, 0, 3]))}
+        mode = int(r.choice([ets.ETS_PLAN_TREE, ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT]))
+        print("case sweep", seed, (hkv, hq), tree.n_nodes, tree.n_leaves, options, mode, flush=True)
+        k, v, q = make_values_host(cfg, tree)
+        oo, ol = oracle_full(cfg, tree, k, v, q)
+        with make_ctx(cfg, options) as ctx:
+            out, lse, _ = run(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q), mode)
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "sweep %d" % seed)
+        ks, vs = float(r.choice([1.0, KS, 0.5])), float(r.choice([1.0, VS, 3.0]))
+        kc, vc, q8 = make_values_fp8_host(cfg, tree, ks, vs)
+        fo, fl = oracle_fp8(cfg, tree, kc, vc, q8, ks, vs)
+        with make_ctx(cfg, options) as ctx:
+            ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, ks, vs)
+            out, lse, _ = run(ctx, tree, pool_to_device(kc), pool_to_device(vc), to_device(q8), mode)
+        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+                fo.reshape(-1, 128), fl.reshape(-1), "bf16", "sweep e4m3 %d" % seed)
+        if seed % 3 == 0 and 0 < int(tree.n_tokens[tree.leaf_node].sum()) < 3000:
+            qs = make_prefill_queries_host(cfg, tree)
+            with make_ctx(cfg) as ctx:
+                po, pl, st = gpu_prefill(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(qs))
+            eo, el = oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens,
+                                              tree.leaf_node, k, v, qs, hkv, hq, 128)
+            compare(po.cpu().numpy().reshape(-1, 128), pl.cpu().numpy().reshape(-1),
+                    eo.reshape(-1, 128), el.reshape(-1), "bf16", "sweep prefill %d" % seed)
