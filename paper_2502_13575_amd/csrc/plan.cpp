@@ -412,6 +412,11 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     p.ent_base.resize((size_t)L);
     for (int32_t i = 0; i < L; ++i) p.ent_base[i] = p.part_base[p.ent_order[i]];
     st.n_partials = p.part_base[L];
+    // the kernels number partial rows, (leaf, head) pairs and workgroups with 32-bit integers
+    const int64_t i32_max = std::numeric_limits<int32_t>::max();
+    if (st.n_partials * shape.n_q_heads >= i32_max || (int64_t)L * shape.n_q_heads >= i32_max ||
+        (int64_t)p.stream_items.size() * shape.n_kv_heads >= i32_max)
+        return ETS_ERR_UNSUPPORTED;
     st.n_stream_items = (int64_t)p.stream_items.size();
     st.n_cascade_items = (int64_t)p.cascade_items.size();
     st.workspace_bytes = st.n_partials * shape.n_q_heads * ((int64_t)shape.head_dim + 2) * 4;
