@@ -207,7 +207,10 @@ def main():
                 "traffic": measured_traffic(cfg.name) if dom == "cascade" else None,
                 "avg_launch_us": round(dom_ms * 1e3, 2),
                 "algorithmic_bytes_per_launch": int(kern[dom][1])}
-    kernel_us = {"stream_attn": round(prof.stream_ms / max(prof.calls, 1) * 1e3, 2),
+    # (without streaming items no such kernel is launched; the event pair then only
+    # measures its own spacing)
+    kernel_us = {"stream_attn": round(prof.stream_ms / max(prof.calls, 1) * 1e3, 2)
+                 if st.n_stream_items > 0 else 0.0,
                  "tree_attn": round(prof.cascade_ms / max(prof.calls, 1) * 1e3, 2),
                  "merge": round(prof.merge_ms / max(prof.calls, 1) * 1e3, 2)}
     log("tree: %.3f ms/step, %.0f leaf-queries/s, unique-KV %.0f GB/s (%.1f%% of peak); "
