@@ -226,6 +226,14 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 typedef enum { ETS_KV_NATIVE = 0, ETS_KV_FP8_E4M3 = 1 } ets_kv_format;
 ets_status ets_set_kv_format(ets_ctx* ctx, int kv_format /* ets_kv_format */, float k_scale,
                              float v_scale);
+/* One scale per kv head instead of one per pool, for ETS_KV_FP8_E4M3 pools:
+ *     K[t,h,d] = k_scales[h] * value(k_code),  V[t,h,d] = v_scales[h] * value(v_code).
+ * k_scales, v_scales: HOST, [n_kv_heads], positive and finite (else ETS_ERR_INVALID_ARG and
+ * nothing changes); copied.  Call after ets_set_kv_format(ctx, ETS_KV_FP8_E4M3, ...)
+ * (ETS_ERR_INVALID_ARG for native pools; a later ets_set_kv_format sets all heads to its
+ * two scales again).  At most 64 kv heads (ETS_ERR_UNSUPPORTED beyond).  The plans stay
+ * valid; calls enqueued earlier keep the scales they were enqueued with. */
+ets_status ets_set_kv_head_scales(ets_ctx* ctx, const float* k_scales, const float* v_scales);
 
 /* One layer of decode attention for every leaf query of the planned tree.
  *   k_pool, v_pool  DEVICE, [n_kv_heads][pool_tokens][head_dim] of shape.dtype (of E4M3

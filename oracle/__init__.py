@@ -208,25 +208,62 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
     return out, lse
 
 
-def tree_decode_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
-                           v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
-    """Decode attention over pools stored as E4M3 codes with one scale each:
-    K[t, h, :] = k_scale * value(k_codes[t, h, :]), V likewise with v_scale; q as bfloat16
-    bit patterns (uint16) or float32.  The definition is tree_decode_attn's on those K and
-    V.  Since the scores are linear in K and the output is linear in V, it is evaluated as
-    attention over the decoded codes with sm_scale * k_scale in place of sm_scale, and the
-    output times v_scale (lse needs nothing: it is taken over the scaled scores)."""
+def _fp8kv(fn, n_first, parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale, v_scale,
+           q, n_kv_heads, n_q_heads, head_dim, sm_scale, rows):
+    """Attention `fn` (decode or step prefill) over pools of E4M3 codes.  The scales are one
+    number per pool or one per kv head.  Scores are linear in K and the output is linear
+    in V, and the kv heads are independent of each other, so each kv head h is evaluated
+    as attention over the decoded codes of that head with sm_scale * k_scale[h] in place
+    of sm_scale, and its outputs are multiplied by v_scale[h]."""
     from .fp8 import decode_e4m3
-    k = decode_e4m3(k_codes)
-    v = decode_e4m3(v_codes)
+    k_codes, v_codes = np.asarray(k_codes), np.asarray(v_codes)
     q = np.asarray(q)
     if q.dtype == np.uint16:
         q = (q.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    q = np.asarray(q, dtype=np.float32)
+    ks = np.broadcast_to(np.asarray(k_scale, dtype=np.float64), (n_kv_heads,))
+    vs = np.broadcast_to(np.asarray(v_scale, dtype=np.float64), (n_kv_heads,))
+    g = n_q_heads // n_kv_heads
     base = float(sm_scale) if sm_scale > 0 else 1.0 / float(np.sqrt(np.float64(head_dim)))
-    out, lse = tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k, v,
-                                np.ascontiguousarray(q, dtype=np.float32), n_kv_heads, n_q_heads,
-                                head_dim, sm_scale=base * float(k_scale), rows=rows)
-    return out * float(v_scale), lse
+    if rows is None:
+        out = np.zeros((n_first, n_q_heads, head_dim), dtype=np.float64)
+        lse = np.zeros((n_first, n_q_heads), dtype=np.float64)
+    else:
+        rows = [np.asarray(r, dtype=np.int32) for r in rows]
+        out = np.zeros((rows[0].shape[0], head_dim), dtype=np.float64)
+        lse = np.zeros((rows[0].shape[0],), dtype=np.float64)
+    for h in range(n_kv_heads):
+        if rows is not None:
+            pick = np.flatnonzero(rows[-1] // g == h)
+            if pick.size == 0:
+                continue
+            sub_rows = [r[pick] for r in rows[:-1]] + [rows[-1][pick] - h * g]
+        else:
+            sub_rows = None
+        kh = decode_e4m3(np.ascontiguousarray(k_codes[:, h:h + 1, :]))
+        vh = decode_e4m3(np.ascontiguousarray(v_codes[:, h:h + 1, :]))
+        qh = np.ascontiguousarray(q[:, h * g:(h + 1) * g, :])
+        o, l = fn(parent, tok_offset, n_tokens, leaf_node, kh, vh, qh, 1, g, head_dim,
+                  sm_scale=base * float(ks[h]), rows=sub_rows)
+        if rows is None:
+            out[:, h * g:(h + 1) * g, :] = o * float(vs[h])
+            lse[:, h * g:(h + 1) * g] = l
+        else:
+            out[pick] = o * float(vs[h])
+            lse[pick] = l
+    return out, lse
+
+
+def tree_decode_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
+                           v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
+    """Decode attention over pools stored as E4M3 codes:
+    K[t, h, :] = k_scale[h] * value(k_codes[t, h, :]), V likewise with v_scale (a scalar
+    stands for the same scale on every kv head); q as bfloat16 bit patterns (uint16) or
+    float32.  The definition is tree_decode_attn's on those K and V (see _fp8kv for how
+    the scales are applied)."""
+    return _fp8kv(tree_decode_attn, np.asarray(leaf_node).shape[0], parent, tok_offset, n_tokens,
+                  leaf_node, k_codes, v_codes, k_scale, v_scale, q, n_kv_heads, n_q_heads, head_dim,
+                  sm_scale, rows)
 
 
 def prefill_q_ptr(n_tokens, leaf_node):
@@ -290,20 +327,12 @@ def tree_prefill_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q
 
 def tree_prefill_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
                             v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale=0.0, rows=None):
-    """Step-prefill attention over pools stored as E4M3 codes with one scale each: the
-    definition of tree_prefill_attn on K = k_scale * value(k_codes), V = v_scale *
-    value(v_codes), evaluated like tree_decode_attn_fp8kv (scores are linear in K, the
-    output in V)."""
-    from .fp8 import decode_e4m3
-    q = np.asarray(q)
-    if q.dtype == np.uint16:
-        q = (q.astype(np.uint32) << np.uint32(16)).view(np.float32)
-    base = float(sm_scale) if sm_scale > 0 else 1.0 / float(np.sqrt(np.float64(head_dim)))
-    out, lse = tree_prefill_attn(parent, tok_offset, n_tokens, leaf_node, decode_e4m3(k_codes),
-                                 decode_e4m3(v_codes), np.ascontiguousarray(q, dtype=np.float32),
-                                 n_kv_heads, n_q_heads, head_dim, sm_scale=base * float(k_scale),
-                                 rows=rows)
-    return out * float(v_scale), lse
+    """Step-prefill attention over pools stored as E4M3 codes with one scale per pool or
+    per kv head: the definition of tree_prefill_attn on K = k_scale[h] * value(k_codes),
+    V = v_scale[h] * value(v_codes)."""
+    n_rows = int(prefill_q_ptr(n_tokens, leaf_node)[-1])
+    return _fp8kv(tree_prefill_attn, n_rows, parent, tok_offset, n_tokens, leaf_node, k_codes,
+                  v_codes, k_scale, v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale, rows)
 
 
 def visible_rows(parent, tok_offset, n_tokens, node, own_rows=None):

@@ -4,7 +4,7 @@ Argument marshalling only: every step of the path runs in the HIP library.
 There is no CPU fallback; loading fails loudly when the library is not built.
 """
 from .binding import (ETS_BF16, ETS_F32, ETS_KV_FP8_E4M3, ETS_KV_NATIVE, ETS_PLAN_FLAT,
-                      ETS_PLAN_TREE, ets_set_kv_format, Context, EtsError,
+                      ETS_PLAN_TREE, ets_set_kv_format, ets_set_kv_head_scales, Context, EtsError,
                       EtsProfile, EtsShape, EtsStats, ets_create, ets_destroy, ets_plan, ets_plan_leaf_counts,
                       ets_plan_leaf_cover, ets_plan_paths, ets_plan_stats, ets_profile_read, ets_set_option,
                       ets_kv_append, ets_plan_advance, EtsPrefillStats, ets_plan_prefill,
@@ -13,7 +13,7 @@ from .binding import (ETS_BF16, ETS_F32, ETS_KV_FP8_E4M3, ETS_KV_NATIVE, ETS_PLA
                       ets_strerror, ets_tree_decode_attn, library_path, load_library)
 
 __all__ = [
-    "ETS_BF16", "ETS_F32", "ETS_KV_NATIVE", "ETS_KV_FP8_E4M3", "ets_set_kv_format",
+    "ETS_BF16", "ETS_F32", "ETS_KV_NATIVE", "ETS_KV_FP8_E4M3", "ets_set_kv_format", "ets_set_kv_head_scales",
     "ETS_PLAN_FLAT", "ETS_PLAN_TREE", "Context", "EtsError", "EtsShape",
     "EtsStats", "EtsProfile", "ets_profile_read", "ets_create", "ets_destroy", "ets_plan", "ets_plan_leaf_counts",
     "ets_plan_leaf_cover", "ets_plan_paths", "ets_plan_stats", "ets_set_option", "ets_strerror",

@@ -107,6 +107,8 @@ def load_library():
     lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
     lib.ets_set_kv_format.restype = C.c_int
     lib.ets_set_kv_format.argtypes = [vp, C.c_int, C.c_float, C.c_float]
+    lib.ets_set_kv_head_scales.restype = C.c_int
+    lib.ets_set_kv_head_scales.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.ets_kv_append.restype = C.c_int
     lib.ets_kv_append.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
     lib.ets_plan_advance.restype = C.c_int
@@ -169,6 +171,16 @@ def ets_set_option(ctx, key: str, value: int):
 def ets_set_kv_format(ctx, kv_format: int, k_scale: float = 1.0, v_scale: float = 1.0):
     _check(load_library().ets_set_kv_format(ctx, int(kv_format), float(k_scale), float(v_scale)),
            "ets_set_kv_format")
+
+
+def ets_set_kv_head_scales(ctx, k_scales, v_scales):
+    k = np.ascontiguousarray(k_scales, dtype=np.float32)
+    v = np.ascontiguousarray(v_scales, dtype=np.float32)
+    if k.ndim != 1 or k.shape != v.shape:
+        raise ValueError("one scale per kv head for each pool")
+    _check(load_library().ets_set_kv_head_scales(ctx, k.ctypes.data_as(C.POINTER(C.c_float)),
+                                                 v.ctypes.data_as(C.POINTER(C.c_float))),
+           "ets_set_kv_head_scales")
 
 
 def _tree_struct(parent, tok_offset, n_tokens, leaf_node):
@@ -374,6 +386,11 @@ class Context:
 
     def set_kv_format(self, kv_format, k_scale=1.0, v_scale=1.0):
         ets_set_kv_format(self._ctx, kv_format, k_scale, v_scale)
+
+    def set_kv_head_scales(self, k_scales, v_scales):
+        if len(k_scales) != self.shape.n_kv_heads or len(v_scales) != self.shape.n_kv_heads:
+            raise ValueError("one scale per kv head for each pool")
+        ets_set_kv_head_scales(self._ctx, k_scales, v_scales)
 
     def plan(self, parent, tok_offset, n_tokens, leaf_node, mode=ETS_PLAN_TREE) -> EtsStats:
         ets_plan(self._ctx, parent, tok_offset, n_tokens, leaf_node, mode)

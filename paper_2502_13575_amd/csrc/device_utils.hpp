@@ -11,6 +11,12 @@ struct bf16_t {
     uint16_t bits;
 };
 
+// One factor per kv head, passed to kernels by value (kernel argument memory).
+constexpr int kMaxScaledHeads = 64;
+struct HeadScales {
+    float s[kMaxScaledHeads];
+};
+
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) {
     return __uint_as_float(packed & 0xFFFF0000u);

@@ -26,7 +26,7 @@ struct ets_ctx {
     PlanOptions opt;
     // variants: pools of E4M3 codes with one scale each; bf16 output
     int kv_format = ETS_KV_NATIVE;
-    float k_scale = 1.f, v_scale = 1.f;
+    HeadScales k_scales{}, v_scales{};  // per kv head; all ones for native pools
     bool out_bf16 = false;
     Plan plan;
     // device copies of the plan's index arrays, carved out of one allocation
@@ -203,13 +203,13 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
                                static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
                                (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
-                               c->scale * c->k_scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+                               c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
         else
             hipLaunchKernelGGL(tree_attn_kernel<false>, dim3((unsigned)c->shape.n_kv_heads, ny),
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
                                static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
                                (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
-                               c->scale * 1.4426950408889634f, a.ws_o, a.ws_ml);
+                               c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
     }
 }
 
@@ -280,24 +280,25 @@ void launch_all(ets_ctx* c, const LaunchArgs& a) {
     mark(c, 2, a.stream);
     const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
     const unsigned grid = (unsigned)((pairs + 3) / 4);
-    const float out_scale = c->kv_format == ETS_KV_FP8_E4M3 ? c->v_scale : 1.f;
+    const HeadScales& out_scale = c->v_scales;
+    const int group = c->shape.n_q_heads / c->shape.n_kv_heads;
     const int n_leaves = (int)c->plan.stats.n_leaves;
     if (c->shape.head_dim == 128 && c->out_bf16)
         hipLaunchKernelGGL((merge_kernel<128, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<bf16_t*>(a.out), a.lse, out_scale);
+                           static_cast<bf16_t*>(a.out), a.lse, out_scale, group);
     else if (c->shape.head_dim == 128)
         hipLaunchKernelGGL((merge_kernel<128, float>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<float*>(a.out), a.lse, out_scale);
+                           static_cast<float*>(a.out), a.lse, out_scale, group);
     else if (c->out_bf16)
         hipLaunchKernelGGL((merge_kernel<64, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<bf16_t*>(a.out), a.lse, out_scale);
+                           static_cast<bf16_t*>(a.out), a.lse, out_scale, group);
     else
         hipLaunchKernelGGL((merge_kernel<64, float>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<float*>(a.out), a.lse, out_scale);
+                           static_cast<float*>(a.out), a.lse, out_scale, group);
     mark(c, 3, a.stream);
     if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
 }
@@ -324,6 +325,7 @@ ets_status ets_create(ets_ctx** out, const ets_shape* shape, int hip_device) {
     c->shape = *shape;
     c->scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / std::sqrt((float)shape->head_dim);
     c->device = hip_device < 0 ? -1 : hip_device;
+    for (int h = 0; h < kMaxScaledHeads; ++h) c->k_scales.s[h] = c->v_scales.s[h] = 1.f;
     *out = c;
     return ETS_OK;
 }
@@ -374,12 +376,30 @@ ets_status ets_set_kv_format(ets_ctx* ctx, int kv_format, float k_scale, float v
         if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
     }
     ctx->kv_format = kv_format;
-    ctx->k_scale = kv_format == ETS_KV_FP8_E4M3 ? k_scale : 1.f;
-    ctx->v_scale = kv_format == ETS_KV_FP8_E4M3 ? v_scale : 1.f;
+    for (int h = 0; h < kMaxScaledHeads; ++h) {
+        ctx->k_scales.s[h] = kv_format == ETS_KV_FP8_E4M3 ? k_scale : 1.f;
+        ctx->v_scales.s[h] = kv_format == ETS_KV_FP8_E4M3 ? v_scale : 1.f;
+    }
     ctx->opt.kv_elem_bytes = kv_format == ETS_KV_FP8_E4M3 ? 1 : 0;
     // byte counts and item sizes of a plan depend on the element size
     ctx->plan.valid = false;
     ctx->prefill.valid = false;
+    return ETS_OK;
+}
+
+ets_status ets_set_kv_head_scales(ets_ctx* ctx, const float* k_scales, const float* v_scales) {
+    if (!ctx || !k_scales || !v_scales) return ETS_ERR_INVALID_ARG;
+    if (ctx->kv_format != ETS_KV_FP8_E4M3) return ETS_ERR_INVALID_ARG;
+    const int n = ctx->shape.n_kv_heads;
+    if (n > kMaxScaledHeads) return ETS_ERR_UNSUPPORTED;
+    for (int h = 0; h < n; ++h)
+        if (!(k_scales[h] > 0.f) || !(v_scales[h] > 0.f) || !std::isfinite(k_scales[h]) ||
+            !std::isfinite(v_scales[h]))
+            return ETS_ERR_INVALID_ARG;
+    for (int h = 0; h < n; ++h) {
+        ctx->k_scales.s[h] = k_scales[h];
+        ctx->v_scales.s[h] = v_scales[h];
+    }
     return ETS_OK;
 }
 
@@ -641,13 +661,14 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
             hipLaunchKernelGGL(prefill_attn_kernel<true>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
                                dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
                                static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
-                               (int)y0, g_shift, ctx->scale * ctx->k_scale * 1.4426950408889634f,
-                               ctx->v_scale, out, lse);
+                               (int)y0, g_shift, ctx->scale * 1.4426950408889634f, ctx->k_scales,
+                               ctx->v_scales, out, lse);
         else
             hipLaunchKernelGGL(prefill_attn_kernel<false>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
                                dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
                                static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
-                               (int)y0, g_shift, ctx->scale * 1.4426950408889634f, 1.0f, out, lse);
+                               (int)y0, g_shift, ctx->scale * 1.4426950408889634f, ctx->k_scales,
+                               ctx->v_scales, out, lse);
     }
     ctx->last_stream = stream;
     ctx->stream_used = true;

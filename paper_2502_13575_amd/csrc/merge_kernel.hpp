@@ -6,7 +6,8 @@
 // are consecutive slots and are combined in slot order, so the result does not
 // depend on scheduling.  A leaf without partials (empty chain) gets out = 0,
 // lse = -inf.  out may be written as fp32 or rounded to bf16 (nearest even), and is
-// multiplied by out_scale first (the scale of a quantised V pool; 1 otherwise).
+// multiplied first by the factor of its kv head (the scale of a quantised V pool; 1
+// otherwise); `group` = query heads per kv head.
 #pragma once
 
 #include "device_utils.hpp"
@@ -26,7 +27,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ 
                                                     const float* __restrict__ ws_o,
                                                     const float2* __restrict__ ws_ml,
                                                     OutT* __restrict__ out,
-                                                    float* __restrict__ lse, float out_scale) {
+                                                    float* __restrict__ lse, HeadScales v_scales,
+                                                    int group) {
     constexpr int EPL = D / 64;  // floats per lane
     struct alignas(4 * EPL) RowPiece {
         float f[EPL];
@@ -89,6 +91,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ 
         }
     }
     const bool empty = p1 == p0;
+    const float out_scale = v_scales.s[j / group];
     const float inv = empty ? 0.f : 1.f / ls;
     if constexpr (sizeof(OutT) == 4) {
         float* dst = reinterpret_cast<float*>(out) + pair * D + lane * EPL;

@@ -167,14 +167,14 @@ __device__ __forceinline__ float prefill_unit(const u32x4_t* __restrict__ ks_nex
 }
 
 // FP8: the pools hold E4M3 codes (128-byte rows, 8 bytes per lane and load); the codes are
-// widened while the tile is staged (K to bf16, V straight to the fp16 fragments), the K
-// scale is part of scale_log2e and the V scale (out_scale) multiplies the normalised rows.
+// widened while the tile is staged (K to bf16, V straight to the fp16 fragments), the kv
+// head's K scale enters the score scale and its V scale multiplies the normalised rows.
 template <bool FP8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ runs,
-    const PrefillItem* __restrict__ items, int item_base, int g_shift, float scale_log2e,
-    float out_scale, float* __restrict__ out, float* __restrict__ lse) {
+    const PrefillItem* __restrict__ items, int item_base, int g_shift, float scale_log2e_base,
+    HeadScales k_scales, HeadScales v_scales, float* __restrict__ out, float* __restrict__ lse) {
     constexpr int D = 128;
     constexpr int KROW = kTreeAttnKRow;
     constexpr int KS_UNITS = 64 * KROW;    // K tile: 64 rows of 272 bytes
@@ -195,6 +195,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     const int n = lane & 31;  // in the matrix layouts: query row / run row / d
     const int g = lane >> 5;
     const int h = blockIdx.x;
+    const float scale_log2e = FP8 ? scale_log2e_base * k_scales.s[h] : scale_log2e_base;
     const PrefillItem it = items[item_base + (int)blockIdx.y];
     const int G = 1 << g_shift;
     const int n_q_heads = n_kv_heads << g_shift;
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     float l = lsum;
     l += __shfl_xor(l, 32, 64);
     float inv = 1.0f / l;
-    if constexpr (FP8) inv *= out_scale;
+    if constexpr (FP8) inv *= v_scales.s[h];
     if (g == 0 && (r_lane >> g_shift) < it.n_tok)
         lse[(it.q_row0 + tq_lane) * n_q_heads + h * G + (r_lane & (G - 1))] =
             (m * scale_log2e + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
     const CascadeItem* __restrict__ items, int wg_base, int n_single, int n_items,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
-    float scale_log2e,
+    float scale_log2e_base, HeadScales k_scales,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
     constexpr int D = 128;
     const int n_kv_heads = (int)gridDim.x;
@@ -244,6 +244,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int a = lane & 15;  // 16-byte piece of a row when loading; MFMA row/column index
     const int b = lane >> 4;  // token sub-index when loading; MFMA contraction group kg
     const int h = blockIdx.x;  // kv head; consecutive workgroups share an item
+    // E4M3 pools: the K scale of this kv head is part of the score scale
+    const float scale_log2e = FP8 ? scale_log2e_base * k_scales.s[h] : scale_log2e_base;
     // workgroups [0, n_single) take one item each; the others hold four small items,
     // one per wave, which then works alone: no barrier below this point on that path
     const int wg = wg_base + (int)blockIdx.y;

@@ -284,3 +284,50 @@ def test_wide_random_sweep():
                                               tree.leaf_node, k, v, qs, hkv, hq, 128)
             compare(po.cpu().numpy().reshape(-1, 128), pl.cpu().numpy().reshape(-1),
                     eo.reshape(-1, 128), el.reshape(-1), "bf16", "sweep prefill %d" % seed)
+
+
+def test_fp8kv_one_scale_per_kv_head():
+    """ets_set_kv_head_scales: decode attention and step prefill with a scale of its own for
+    every kv head and pool, against the oracle; a later ets_set_kv_format returns every
+    head to the per-pool scales; bad arguments change nothing."""
+    from workload import make_prefill_queries_host
+    cfg = CONFIGS["c3_pruned"]
+    tree = make_tree(cfg)
+    r = np.random.default_rng(4)
+    # (scales at most those the codes were made with: V stays of unit size, for which the
+    # absolute bar is meant)
+    ks = r.uniform(0.3 * KS, KS, size=cfg.n_kv_heads).astype(np.float32)
+    vs = r.uniform(0.3 * VS, VS, size=cfg.n_kv_heads).astype(np.float32)
+    kc, vc, q = make_values_fp8_host(cfg, tree, KS, VS)
+    qs = make_prefill_queries_host(cfg, tree)
+    kd, vd = pool_to_device(kc), pool_to_device(vc)
+    with make_ctx(cfg) as ctx:
+        with pytest.raises(ets.EtsError) as e:
+            ctx.set_kv_head_scales(ks, vs)               # native pools have no scales
+        assert e.value.status == 1
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, KS, VS)
+        ctx.set_kv_head_scales(ks, vs)
+        bad = ks.copy()
+        bad[3] = 0.0
+        with pytest.raises(ets.EtsError) as e:
+            ctx.set_kv_head_scales(bad, vs)
+        assert e.value.status == 1
+        out, lse, _ = run(ctx, tree, kd, vd, to_device(q))
+        outp, lsep, _ = gpu_prefill(ctx, tree, kd, vd, to_device(qs))
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, KS, VS)
+        out1, lse1, _ = run(ctx, tree, kd, vd, to_device(q))
+    oo, ol = oracle_fp8(cfg, tree, kc, vc, q, ks.astype(np.float64), vs.astype(np.float64))
+    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "per-head scales decode")
+    n = 80
+    sl = r.integers(0, tree.n_leaves, size=n).astype(np.int32)
+    stok = (r.random(n) * tree.n_tokens[tree.leaf_node[sl]]).astype(np.int32)
+    sh = r.integers(0, cfg.n_q_heads, size=n).astype(np.int32)
+    rows = oracle.prefill_q_ptr(tree.n_tokens, tree.leaf_node)[sl] + stok
+    po, pl = oracle_prefill_fp8(cfg, tree, kc, vc, qs, ks.astype(np.float64),
+                                vs.astype(np.float64), rows=(sl, stok, sh))
+    compare(outp.cpu().numpy()[rows, sh], lsep.cpu().numpy()[rows, sh], po, pl, "bf16",
+            "per-head scales prefill")
+    o1, l1 = oracle_fp8(cfg, tree, kc, vc, q)
+    compare(out1.cpu().numpy().reshape(-1, 128), lse1.cpu().numpy().reshape(-1),
+            o1.reshape(-1, 128), l1.reshape(-1), "bf16", "back to per-pool scales")

@@ -62,8 +62,8 @@ def test_e4m3_structure():
 
 def _dense_reference(tree, kc, vc, ks, vs, q_bits, hkv, hq, d, sm_scale):
     """Softmax attention over each leaf's chain on explicitly dequantised pools, numpy fp64."""
-    K = E4M3_TABLE[kc] * ks
-    V = E4M3_TABLE[vc] * vs
+    K = E4M3_TABLE[kc] * np.broadcast_to(np.asarray(ks, np.float64), (hkv,))[None, :, None]
+    V = E4M3_TABLE[vc] * np.broadcast_to(np.asarray(vs, np.float64), (hkv,))[None, :, None]
     Q = bf16_bits_to_f32(q_bits).astype(np.float64)
     g = hq // hkv
     L = tree.n_leaves
@@ -179,4 +179,31 @@ def test_fp8kv_prefill_against_dense_masked_softmax_and_the_bf16_oracle():
     b = oracle.tree_prefill_attn(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
                                  to_bf16_bits(decode_e4m3(kc)), to_bf16_bits(decode_e4m3(vc)), q,
                                  hkv, hq, d)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_fp8kv_attention_with_one_scale_per_kv_head():
+    """One scale per kv head and pool: decode attention (all rows and picked rows) against
+    the dense fp64 softmax on explicitly dequantised pools."""
+    cfg = CONFIGS["c2_w16"]
+    r = np.random.default_rng(21)
+    ks = r.uniform(0.01, 2.0, size=8)
+    vs = r.uniform(0.01, 3.0, size=8)
+    tree = random_tree(61, 30, 9, 24)
+    kc, vc, q = make_values_fp8_host(cfg, tree, 1.0, 1.0, seed=3)
+    out, lse = oracle.tree_decode_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens,
+                                             tree.leaf_node, kc, vc, ks, vs, q, 8, 32, 128)
+    ro, rl = _dense_reference(tree, kc, vc, ks, vs, q, 8, 32, 128, 1.0 / math.sqrt(128))
+    assert np.allclose(out, ro, rtol=1e-10, atol=1e-12)
+    fin = np.isfinite(rl)
+    assert np.array_equal(fin, np.isfinite(lse)) and np.allclose(lse[fin], rl[fin], rtol=1e-12)
+    sel = (np.array([0, 8, 3, 3, 5], np.int32), np.array([31, 0, 12, 13, 4], np.int32))
+    o2, l2 = oracle.tree_decode_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens,
+                                           tree.leaf_node, kc, vc, ks, vs, q, 8, 32, 128, rows=sel)
+    assert np.array_equal(o2, out[sel[0], sel[1]]) and np.array_equal(l2, lse[sel[0], sel[1]])
+    # a scalar is the same scale on every head
+    a = oracle.tree_decode_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                      kc, vc, 0.3, 0.7, q, 8, 32, 128)
+    b = oracle.tree_decode_attn_fp8kv(tree.parent, tree.tok_offset, tree.n_tokens, tree.leaf_node,
+                                      kc, vc, np.full(8, 0.3), np.full(8, 0.7), q, 8, 32, 128)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
