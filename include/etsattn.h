@@ -258,6 +258,25 @@ ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_
                                 int64_t pool_tokens, const void* q, void* out, float* lse,
                                 void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* The same call for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The partial results go to a buffer of ETS_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (one per GPU, held until the process ends; its address on the
+ * context's device is looked up by ets_create).  Arguments and result are those of
+ * ets_tree_decode_attn without `workspace`; same kernels, same bits.
+ *   - a plan whose stats.workspace_bytes exceeds ETS_STATIC_SCRATCH_BYTES is refused with
+ *     ETS_ERR_WORKSPACE (nothing is enqueued);
+ *   - the call allocates nothing on host or device and records no profiling events
+ *     (the "profile" option does not apply to it);
+ *   - every call on one GPU uses that GPU's one buffer, whatever the context: calls that
+ *     may overlap on a GPU (different streams without ordering between them) race.  Calls
+ *     on one stream, or ordered by events, are safe; nothing has to be cleared between
+ *     calls (every partial row is written before it is read). */
+#define ETS_STATIC_SCRATCH_BYTES (32ll << 20)
+ets_status ets_tree_decode_attn_static(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                       int64_t pool_tokens, const void* q, void* out, float* lse,
+                                       void* hip_stream);
+
 /* Kernel times for benchmarks.  After ets_set_option(ctx, "profile", 1) every
  * ets_tree_decode_attn call brackets its kernels with HIP events on the call's
  * stream (this mode may create events, i.e. allocate; at most 8192 calls are

@@ -10,7 +10,8 @@ from .binding import (ETS_BF16, ETS_F32, ETS_KV_FP8_E4M3, ETS_KV_NATIVE, ETS_PLA
                       ets_kv_append, ets_plan_advance, EtsPrefillStats, ets_plan_prefill,
                       ets_prefill_plan_stats, ets_prefill_q_ptr, ets_prefill_cover,
                       ets_tree_prefill_attn, EtsSelectInfo, ets_rebase_weights, ets_select_leaves,
-                      ets_strerror, ets_tree_decode_attn, library_path, load_library)
+                      ets_strerror, ets_tree_decode_attn, ets_tree_decode_attn_static,
+                      ETS_STATIC_SCRATCH_BYTES, library_path, load_library)
 
 __all__ = [
     "ETS_BF16", "ETS_F32", "ETS_KV_NATIVE", "ETS_KV_FP8_E4M3", "ets_set_kv_format", "ets_set_kv_head_scales",
@@ -20,5 +21,6 @@ __all__ = [
     "ets_kv_append", "ets_plan_advance", "EtsPrefillStats", "ets_plan_prefill",
     "ets_prefill_plan_stats", "ets_prefill_q_ptr", "ets_prefill_cover", "ets_tree_prefill_attn",
     "EtsSelectInfo", "ets_rebase_weights", "ets_select_leaves",
-    "ets_tree_decode_attn", "library_path", "load_library",
+    "ets_tree_decode_attn", "ets_tree_decode_attn_static", "ETS_STATIC_SCRATCH_BYTES",
+    "library_path", "load_library",
 ]

@@ -11,6 +11,7 @@ import numpy as np
 ETS_F32, ETS_BF16 = 0, 1
 ETS_PLAN_TREE, ETS_PLAN_FLAT = 0, 1
 ETS_KV_NATIVE, ETS_KV_FP8_E4M3 = 0, 1
+ETS_STATIC_SCRATCH_BYTES = 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libetsattn.so")
@@ -105,6 +106,8 @@ def load_library():
     lib.ets_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
     lib.ets_tree_decode_attn.restype = C.c_int
     lib.ets_tree_decode_attn.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp]
+    lib.ets_tree_decode_attn_static.restype = C.c_int
+    lib.ets_tree_decode_attn_static.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp, vp]
     lib.ets_set_kv_format.restype = C.c_int
     lib.ets_set_kv_format.argtypes = [vp, C.c_int, C.c_float, C.c_float]
     lib.ets_set_kv_head_scales.restype = C.c_int
@@ -300,6 +303,14 @@ def ets_tree_decode_attn(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse, wor
         "ets_tree_decode_attn")
 
 
+def ets_tree_decode_attn_static(ctx, k_pool, v_pool, pool_tokens: int, q, out, lse,
+                                hip_stream=None):
+    stream = None if hip_stream is None else C.c_void_p(int(hip_stream))
+    _check(load_library().ets_tree_decode_attn_static(
+        ctx, _dev_ptr(k_pool), _dev_ptr(v_pool), int(pool_tokens), _dev_ptr(q), _dev_ptr(out),
+        _dev_ptr(lse), stream), "ets_tree_decode_attn_static")
+
+
 def ets_kv_append(ctx, k_pool, v_pool, pool_tokens: int, k_new, v_new, stream=None) -> None:
     st = None if stream is None else C.c_void_p(int(stream))
     _check(load_library().ets_kv_append(ctx, _dev_ptr(k_pool), _dev_ptr(v_pool), int(pool_tokens),
@@ -437,3 +448,7 @@ class Context:
                hip_stream=None):
         ets_tree_decode_attn(self._ctx, k_pool, v_pool, pool_tokens, q, out, lse, workspace,
                              workspace_bytes, hip_stream)
+
+    def decode_static(self, k_pool, v_pool, pool_tokens, q, out, lse, hip_stream=None):
+        ets_tree_decode_attn_static(self._ctx, k_pool, v_pool, pool_tokens, q, out, lse,
+                                    hip_stream)

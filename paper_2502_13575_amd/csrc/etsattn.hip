@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -49,13 +50,39 @@ struct ets_ctx {
     PrefillItem* d_pre_items = nullptr;
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
+    void* static_scratch = nullptr;  // this device's copy of `scratch` (null: host-only context)
     // kernel timing (benchmarks only): four events per recorded call
     bool profile = false;
     std::vector<hipEvent_t> events;
     size_t calls_recorded = 0;
 };
 
+// Partial results of ets_tree_decode_attn_static: part of the device image, so that the call
+// needs no allocation.  In host code the array's name only stands for the symbol; its
+// device address is looked up per GPU (scratch_on_device) and that pointer is what the
+// kernels receive.
+static __device__ __align__(256) unsigned char scratch[ETS_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // the array's address on every device seen so far
+
+// Address of `scratch` on `device`, which has to be current.  Looked up once per device.
+void* scratch_on_device(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
 
 // Makes the context's device current for the scope of a call.
 struct DeviceGuard {
@@ -265,8 +292,11 @@ void mark(ets_ctx* c, int which, hipStream_t stream) {
     (void)hipEventRecord(c->events[idx], stream);
 }
 
-void launch_all(ets_ctx* c, const LaunchArgs& a) {
+// `timed`: bracket the kernels with events when the "profile" option is on (may allocate)
+void launch_all(ets_ctx* c, const LaunchArgs& a, bool timed) {
     const bool bf = c->shape.dtype == ETS_BF16;
+    const bool was_profiling = c->profile;
+    if (!timed) c->profile = false;
     mark(c, 0, a.stream);
     if (c->shape.head_dim == 128) {
         if (bf) launch_stream_g<bf16_t, 128>(c, a);
@@ -301,9 +331,52 @@ void launch_all(ets_ctx* c, const LaunchArgs& a) {
                            static_cast<float*>(a.out), a.lse, out_scale, group);
     mark(c, 3, a.stream);
     if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
+    if (!timed) c->profile = was_profiling;
 }
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Argument checks and launches shared by the two decode entry points.
+ets_status decode_call(ets_ctx* ctx, const void* k_pool, const void* v_pool, int64_t pool_tokens,
+                       const void* q, void* out, float* lse, void* workspace,
+                       int64_t workspace_bytes, void* hip_stream, bool timed) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    const ets_stats& st = ctx->plan.stats;
+    if (st.n_leaves == 0) return ETS_OK;
+    if (!q || !out || !lse || pool_tokens < 0 || workspace_bytes < 0) return ETS_ERR_INVALID_ARG;
+    if (st.unique_tokens > 0 && (!k_pool || !v_pool)) return ETS_ERR_INVALID_ARG;
+    if (pool_tokens < st.min_pool_tokens) return ETS_ERR_BAD_TREE;
+    // E4M3 pools are read by the matrix-core kernel only
+    if (ctx->kv_format == ETS_KV_FP8_E4M3 && !ctx->plan.stream_items.empty())
+        return ETS_ERR_UNSUPPORTED;
+    if (workspace_bytes < st.workspace_bytes || (st.workspace_bytes > 0 && !workspace))
+        return ETS_ERR_WORKSPACE;
+    if (misaligned(k_pool) || misaligned(v_pool) || misaligned(q) || misaligned(out) ||
+        misaligned(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return ETS_ERR_INVALID_ARG;
+
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    LaunchArgs a;
+    a.k = k_pool;
+    a.v = v_pool;
+    a.q = q;
+    a.pool_tokens = pool_tokens;
+    a.out = out;
+    a.lse = lse;
+    a.ws_o = static_cast<float*>(workspace);
+    a.ws_ml = reinterpret_cast<float2*>(a.ws_o + st.n_partials * ctx->shape.n_q_heads *
+                                                     (int64_t)ctx->shape.head_dim);
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    launch_all(ctx, a, timed);
+    ctx->last_stream = a.stream;
+    ctx->stream_used = true;
+    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
+    return ETS_OK;
+}
 
 }  // namespace
 
@@ -326,6 +399,16 @@ ets_status ets_create(ets_ctx** out, const ets_shape* shape, int hip_device) {
     c->scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / std::sqrt((float)shape->head_dim);
     c->device = hip_device < 0 ? -1 : hip_device;
     for (int h = 0; h < kMaxScaledHeads; ++h) c->k_scales.s[h] = c->v_scales.s[h] = 1.f;
+    if (c->device >= 0) {
+        // set-up is the place for the symbol look-up: ets_tree_decode_attn_static must not
+        // do anything that could allocate
+        DeviceGuard guard(c->device);
+        c->static_scratch = guard.ok ? scratch_on_device(c->device) : nullptr;
+        if (!c->static_scratch) {
+            delete c;
+            return ETS_ERR_HIP;
+        }
+    }
     *out = c;
     return ETS_OK;
 }
@@ -550,42 +633,18 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
 ets_status ets_tree_decode_attn(ets_ctx* ctx, const void* k_pool, const void* v_pool,
                                 int64_t pool_tokens, const void* q, void* out, float* lse,
                                 void* workspace, int64_t workspace_bytes, void* hip_stream) {
-    if (!ctx) return ETS_ERR_INVALID_ARG;
-    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
-    if (ctx->device < 0) return ETS_ERR_HIP;
-    const ets_stats& st = ctx->plan.stats;
-    if (st.n_leaves == 0) return ETS_OK;
-    if (!q || !out || !lse || pool_tokens < 0 || workspace_bytes < 0) return ETS_ERR_INVALID_ARG;
-    if (st.unique_tokens > 0 && (!k_pool || !v_pool)) return ETS_ERR_INVALID_ARG;
-    if (pool_tokens < st.min_pool_tokens) return ETS_ERR_BAD_TREE;
-    // E4M3 pools are read by the matrix-core kernel only
-    if (ctx->kv_format == ETS_KV_FP8_E4M3 && !ctx->plan.stream_items.empty())
-        return ETS_ERR_UNSUPPORTED;
-    if (workspace_bytes < st.workspace_bytes || (st.workspace_bytes > 0 && !workspace))
-        return ETS_ERR_WORKSPACE;
-    if (misaligned(k_pool) || misaligned(v_pool) || misaligned(q) || misaligned(out) ||
-        misaligned(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
-        return ETS_ERR_INVALID_ARG;
+    return decode_call(ctx, k_pool, v_pool, pool_tokens, q, out, lse, workspace, workspace_bytes,
+                       hip_stream, true);
+}
 
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return ETS_ERR_HIP;
-    LaunchArgs a;
-    a.k = k_pool;
-    a.v = v_pool;
-    a.q = q;
-    a.pool_tokens = pool_tokens;
-    a.out = out;
-    a.lse = lse;
-    a.ws_o = static_cast<float*>(workspace);
-    a.ws_ml = reinterpret_cast<float2*>(a.ws_o + st.n_partials * ctx->shape.n_q_heads *
-                                                     (int64_t)ctx->shape.head_dim);
-    a.stream = static_cast<hipStream_t>(hip_stream);
-    (void)hipGetLastError();
-    launch_all(ctx, a);
-    ctx->last_stream = a.stream;
-    ctx->stream_used = true;
-    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
-    return ETS_OK;
+ets_status ets_tree_decode_attn_static(ets_ctx* ctx, const void* k_pool, const void* v_pool,
+                                       int64_t pool_tokens, const void* q, void* out, float* lse,
+                                       void* hip_stream) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (ctx->device < 0) return ETS_ERR_HIP;
+    // ctx->static_scratch is the device address found at ets_create, never the symbol itself
+    return decode_call(ctx, k_pool, v_pool, pool_tokens, q, out, lse, ctx->static_scratch,
+                       ETS_STATIC_SCRATCH_BYTES, hip_stream, false);
 }
 
 ets_status ets_plan_prefill(ets_ctx* ctx, const ets_tree* tree) {
