@@ -58,7 +58,16 @@ typedef enum { ETS_F32 = 0, ETS_BF16 = 1 } ets_dtype;
 /* Element type and head geometry of the pools and of q.
  * Supported: head_dim in {64, 128}; n_q_heads = G * n_kv_heads with G in
  * {1, 2, 4, 8} (query head j reads kv head j / G).  sm_scale <= 0 selects
- * 1/sqrt(head_dim). */
+ * 1/sqrt(head_dim).
+ *
+ * Which shapes get the method.  Reading every shared node once per call for all the
+ * leaves beneath it is built for bfloat16 pools with head_dim 128 (the shapes of the
+ * paper's models).  Every other accepted shape -- fp32 pools, which exist as a correctness
+ * path, and head_dim 64 -- gives the same result through the per-leaf kernel: every leaf
+ * query reads its whole chain itself (shared rows come out of the caches, not out of the
+ * plan), at the cost of the flat baseline.  ets_stats.shares_nodes says which of the two a
+ * plan is, and with the option "require_sharing" ets_plan refuses (ETS_ERR_UNSUPPORTED) a
+ * tree-mode plan that would not share. */
 typedef struct {
     int32_t n_kv_heads;
     int32_t n_q_heads;
@@ -109,6 +118,8 @@ typedef struct {
     int64_t workspace_bytes; /* device scratch ets_tree_decode_attn needs                */
     int64_t cascade_tokens;  /* unique tokens read (once) by the shared-node kernel      */
     int64_t stream_tokens;   /* tokens read by the streaming kernel, repeats included    */
+    int64_t shares_nodes;    /* 1: shared nodes are read once per call (bf16, head_dim   */
+                             /* 128, tree mode); 0: every leaf reads its chain itself    */
 } ets_stats;
 
 typedef enum {
@@ -153,16 +164,50 @@ ets_status ets_plan_leaf_counts(const ets_ctx* ctx, int64_t* leaf_count);
 ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, int64_t cap,
                                int64_t* n_rows, int32_t* n_partials);
 
+/* Replays on the host what the kernels of the current plans (decode and, when present,
+ * step prefill) will read and write, from the same tables the kernels read: every step's
+ * rows against min_pool_tokens, every index a wavefront loads from the per-leaf-query
+ * tables against their padded size, the leaf queries whose q rows it fetches, the partial
+ * rows it writes against the workspace.  ETS_OK when everything is in bounds;
+ * ETS_ERR_BAD_TREE otherwise (a planner defect: the plan must not be launched).  *report
+ * (HOST, may be NULL) is filled either way.  Works without a device. */
+typedef struct {
+    int64_t decode_items;         /* work items replayed (both kernels)                        */
+    int64_t prefill_items;        /* 0 without a prefill plan                                  */
+    int64_t entry_table_entries;  /* entries of each per-leaf-query table, padding included    */
+    int64_t max_entry_index;      /* highest entry index any wavefront loads                   */
+    int64_t max_entry_overreach;  /* entries loaded past an item's own last entry, at most     */
+    int64_t max_pool_row;         /* highest pool row any step names                           */
+    int64_t max_partial_row;      /* highest (partial, head) row written                       */
+    int64_t violations;
+} ets_plan_check_report;
+ets_status ets_plan_check(const ets_ctx* ctx, ets_plan_check_report* report);
+
 /* Decode-step advance.  Between two decode tokens of one search step the tree's
  * topology is fixed and only the nodes that hold leaf queries grow, by one token each
  * (ETS paper, Sec. 4.1: the tree changes once per step; App. B: leaves are the latest
  * steps).  Per decode token the caller runs, on one stream and in this order:
- * ets_kv_append, ets_plan_advance, then ets_tree_decode_attn for every layer (a layer's
- * append may also directly precede that layer's attention call, with the advance first).
+ *     ets_plan_advance                      once: the plan now counts the new token
+ *     for every layer:  ets_kv_append       the new token's K/V rows into that layer's pools
+ *                       ets_tree_decode_attn
+ * (a layer's K/V of the new token depend on the previous layer's attention output, so the
+ * appends cannot all precede the first attention call; this order serves one pool and
+ * many alike).
  *
- * ets_kv_append writes, for every distinct node of leaf_node, one new row of K and V
- * at pool row tok_offset[node] + n_tokens[node] (the plan's current lengths), which
- * the caller must have reserved for that node.
+ * ets_plan_advance makes every distinct node of leaf_node one token longer in the plan
+ * (the library's copy of the tree, statistics, and the step lists on the device, the
+ * latter through a small kernel on hip_stream).  The step lists have room for at
+ * least 32 advances; when it is used up the call plans again from its grown copy of
+ * the tree (this waits for the context's previous work, like ets_plan) and sets
+ * *replanned (may be NULL) to 1: n_partials and workspace_bytes may then have changed
+ * and are to be read again with ets_plan_stats.  Works without a device too.
+ *
+ * ets_kv_append writes, for every distinct node of leaf_node, one row of K and V at the
+ * node's NEWEST row as the plan counts it, tok_offset[node] + n_tokens[node] - 1: after an
+ * ets_plan_advance that is the row of the token the advance added (which the caller must
+ * have reserved behind the node); on a plan that was just built it is the last row the
+ * caller's tree named.  The row does not depend on how many layers have been appended
+ * before.  A node without rows is skipped.
  *   k_pool, v_pool  DEVICE, as in ets_tree_decode_attn (same element size), written
  *   pool_tokens     rows per head plane, as in ets_tree_decode_attn; must exceed
  *                   every written row, else ETS_ERR_INVALID_ARG and nothing is written
@@ -171,16 +216,13 @@ ets_status ets_plan_leaf_cover(const ets_ctx* ctx, int32_t leaf, int64_t* rows, 
  *                   queries sit on one node, the first of them supplies the row
  * Asynchronous on hip_stream; no allocation.
  *
- * ets_plan_advance makes every distinct node of leaf_node one token longer in the plan
- * (the library's copy of the tree, statistics, and the step lists on the device, the
- * latter through a small kernel on hip_stream).  The step lists have room for at
- * least 32 advances; when it is used up the call plans again from its grown copy of
- * the tree (this waits for the context's previous work, like ets_plan) and sets
- * *replanned (may be NULL) to 1: n_partials and workspace_bytes may then have changed
- * and are to be read again with ets_plan_stats.  Works without a device too. */
+ * ets_plan_append_rows reports where ets_kv_append would write now: rows[l] (HOST,
+ * [n_leaves]) = the pool row that receives row l of k_new / v_new, or -1 when leaf query l
+ * supplies none (a later leaf query of a node, or a node without rows). */
 ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_tokens,
                          const void* k_new, const void* v_new, void* hip_stream);
 ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned);
+ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
 
 /* Planner knobs, effective from the next ets_plan.  Keys:
  *   "stream_chunk"   max tokens per work item of a single leaf query (0 = auto)
@@ -195,6 +237,10 @@ ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned);
  *   "wave_items"     a work item of at most 16 query rows and at most this many
  *                    tokens is walked by a single wavefront, four such items to
  *                    a workgroup (default 512; 0 = every item gets a workgroup)
+ *   "require_sharing"  1 = ets_plan in tree mode returns ETS_ERR_UNSUPPORTED when this
+ *                    context cannot read shared nodes once (shape other than bf16 /
+ *                    head_dim 128, or "mfma" / "cascade_min_leaves" set to 0) instead
+ *                    of falling back to per-leaf reads; 0 (default) = fall back
  *   "mfma"           1 (default) = matrix-core kernel for bf16 pools with
  *                    head_dim 128; 0 = vector-ALU kernel for every shape (each
  *                    leaf then reads its whole chain itself)
@@ -290,6 +336,20 @@ typedef struct {
 } ets_profile;
 ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out /* host */);
 
+/* Benchmark hook: one plain streaming read of buf[0, bytes) on hip_device (16 bytes per
+ * lane and load, consecutive lanes on consecutive addresses; bytes past the last multiple
+ * of 16 are not read), so that a benchmark can state the attention kernels' unique-KV
+ * GB/s also against the read rate this device sustains in the same run, not only against
+ * the published HBM peak (the paper's premise, Sec. 1 and Sec. 3, is that these reads bound
+ * the search).  nontemporal != 0 uses loads that bypass cache allocation, as the
+ * attention kernel does for rows nobody re-reads.
+ *   buf    DEVICE, 16-byte aligned
+ *   sink   DEVICE, sink_bytes >= 16384, 4-byte aligned, zero or anything: one word per
+ *          workgroup is XOR-ed into it (keeps the loads alive; contents meaningless)
+ * Asynchronous on hip_stream; no allocation.  ETS_ERR_WORKSPACE when sink is too small. */
+ets_status ets_bench_read_stream(int hip_device, const void* buf, int64_t bytes, int nontemporal,
+                                 void* sink, int64_t sink_bytes, void* hip_stream);
+
 /* ---- Step prefill: scoring a newly generated step with the reward model ----------
  *
  * The search scores every candidate step with a process reward model (ETS paper,
@@ -353,14 +413,15 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
 /* ---- The selection step that produces the tree (host only, no context) ---------------
  *
  * ETS decides at every search step which trajectories to keep (ETS paper Sec. 4.1-4.2;
- * App. A).  ets_rebase_weights is Eq. 1 (and Eq. 3 when called on the kept set): the
+ * App. B).  ets_rebase_weights is Eq. 1 (and Eq. 3 when called on the kept set): the
  * trajectories are visited from the highest reward to the lowest, equal rewards in input
  * order; trajectory i receives W_i = ceil(N_i e_i / sum_{k in A_i} e_k) continuations,
  * e = exp(R / temperature), A_i = i and everything after it, N_1 = budget and
  * N_{i+1} = N_i - W_i (the recurrence the paper implies); fp64.
  *   rewards  HOST [n];  weights  HOST [n], written;  budget >= 0, temperature > 0.
  *
- * ets_select_leaves maximises the cost model of Eq. 5 / Eq. 7 exactly:
+ * ets_select_leaves maximises the cost model of Eq. 4 (Eq. 2 when cluster is NULL; the ILPs of App. B,
+ * Eq. 7 and Eq. 6) exactly:
  *     sum_{i kept} W_i / sum_i W_i  -  lambda_b |V_S| / |V_A|  +  lambda_d |C_S| / |C_A|
  * V_A = the nodes with a leaf at or beneath them, V_S = those with a KEPT leaf at or
  * beneath them, C_A / C_S = the clusters present / with a kept leaf (the text's reading

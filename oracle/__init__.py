@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tree_attn_oracle.c")
 _LIB = os.path.join(_HERE, "libets_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F64 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -89,7 +89,9 @@ def _vals(a):
         return a, F32
     if a.dtype == np.uint16:
         return a, BF16
-    raise TypeError("values must be float32 or uint16 (bfloat16 bits), got %s" % a.dtype)
+    if a.dtype == np.float64:
+        return a, F64
+    raise TypeError("values must be float32, float64 or uint16 (bfloat16 bits), got %s" % a.dtype)
 
 
 def _pool(a):
@@ -104,8 +106,10 @@ def _pool(a):
         dt = F32
     elif a.dtype == np.uint16:
         dt = BF16
+    elif a.dtype == np.float64:
+        dt = F64
     else:
-        raise TypeError("values must be float32 or uint16 (bfloat16 bits), got %s" % a.dtype)
+        raise TypeError("values must be float32, float64 or uint16 (bfloat16 bits), got %s" % a.dtype)
     sz = a.dtype.itemsize
     if a.shape[2] > 1 and a.strides[2] != sz or a.strides[0] % sz or a.strides[1] % sz \
             or a.strides[0] < 0 or a.strides[1] < 0:
@@ -208,50 +212,31 @@ def tree_decode_attn(parent, tok_offset, n_tokens, leaf_node, k_pool, v_pool, q,
     return out, lse
 
 
-def _fp8kv(fn, n_first, parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale, v_scale,
+def dequantise_e4m3(codes, scale):
+    """fp64 pool [pool row, kv head, D] from E4M3 codes (uint8, same shape) and one scale per
+    pool or per kv head: value(code) * scale[h], the product taken in fp64."""
+    from .fp8 import E4M3_TABLE
+    codes = np.asarray(codes)
+    if codes.dtype != np.uint8 or codes.ndim != 3:
+        raise TypeError("E4M3 pools travel as uint8 [pool row, kv head, head_dim]")
+    s = np.broadcast_to(np.asarray(scale, dtype=np.float64), (codes.shape[1],))
+    return E4M3_TABLE[codes] * s[None, :, None]
+
+
+def _fp8kv(fn, parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale, v_scale,
            q, n_kv_heads, n_q_heads, head_dim, sm_scale, rows):
-    """Attention `fn` (decode or step prefill) over pools of E4M3 codes.  The scales are one
-    number per pool or one per kv head.  Scores are linear in K and the output is linear
-    in V, and the kv heads are independent of each other, so each kv head h is evaluated
-    as attention over the decoded codes of that head with sm_scale * k_scale[h] in place
-    of sm_scale, and its outputs are multiplied by v_scale[h]."""
-    from .fp8 import decode_e4m3
-    k_codes, v_codes = np.asarray(k_codes), np.asarray(v_codes)
+    """Attention `fn` (decode or step prefill) over pools of E4M3 codes, by the definition:
+    the pools are dequantised to fp64 first (K = k_scale[h] * value(code), V likewise), then
+    `fn` runs once on them with the caller's sm_scale.  q (bfloat16 bits or float32) is
+    widened to fp64 exactly."""
     q = np.asarray(q)
     if q.dtype == np.uint16:
         q = (q.astype(np.uint32) << np.uint32(16)).view(np.float32)
-    q = np.asarray(q, dtype=np.float32)
-    ks = np.broadcast_to(np.asarray(k_scale, dtype=np.float64), (n_kv_heads,))
-    vs = np.broadcast_to(np.asarray(v_scale, dtype=np.float64), (n_kv_heads,))
-    g = n_q_heads // n_kv_heads
-    base = float(sm_scale) if sm_scale > 0 else 1.0 / float(np.sqrt(np.float64(head_dim)))
-    if rows is None:
-        out = np.zeros((n_first, n_q_heads, head_dim), dtype=np.float64)
-        lse = np.zeros((n_first, n_q_heads), dtype=np.float64)
-    else:
-        rows = [np.asarray(r, dtype=np.int32) for r in rows]
-        out = np.zeros((rows[0].shape[0], head_dim), dtype=np.float64)
-        lse = np.zeros((rows[0].shape[0],), dtype=np.float64)
-    for h in range(n_kv_heads):
-        if rows is not None:
-            pick = np.flatnonzero(rows[-1] // g == h)
-            if pick.size == 0:
-                continue
-            sub_rows = [r[pick] for r in rows[:-1]] + [rows[-1][pick] - h * g]
-        else:
-            sub_rows = None
-        kh = decode_e4m3(np.ascontiguousarray(k_codes[:, h:h + 1, :]))
-        vh = decode_e4m3(np.ascontiguousarray(v_codes[:, h:h + 1, :]))
-        qh = np.ascontiguousarray(q[:, h * g:(h + 1) * g, :])
-        o, l = fn(parent, tok_offset, n_tokens, leaf_node, kh, vh, qh, 1, g, head_dim,
-                  sm_scale=base * float(ks[h]), rows=sub_rows)
-        if rows is None:
-            out[:, h * g:(h + 1) * g, :] = o * float(vs[h])
-            lse[:, h * g:(h + 1) * g] = l
-        else:
-            out[pick] = o * float(vs[h])
-            lse[pick] = l
-    return out, lse
+    q = np.asarray(q, dtype=np.float64)
+    k64 = dequantise_e4m3(k_codes, k_scale)
+    v64 = dequantise_e4m3(v_codes, v_scale)
+    return fn(parent, tok_offset, n_tokens, leaf_node, k64, v64, q, n_kv_heads, n_q_heads,
+              head_dim, sm_scale=sm_scale, rows=rows)
 
 
 def tree_decode_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_codes, k_scale,
@@ -259,9 +244,8 @@ def tree_decode_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_c
     """Decode attention over pools stored as E4M3 codes:
     K[t, h, :] = k_scale[h] * value(k_codes[t, h, :]), V likewise with v_scale (a scalar
     stands for the same scale on every kv head); q as bfloat16 bit patterns (uint16) or
-    float32.  The definition is tree_decode_attn's on those K and V (see _fp8kv for how
-    the scales are applied)."""
-    return _fp8kv(tree_decode_attn, np.asarray(leaf_node).shape[0], parent, tok_offset, n_tokens,
+    float32.  The definition is tree_decode_attn's on those K and V."""
+    return _fp8kv(tree_decode_attn, parent, tok_offset, n_tokens,
                   leaf_node, k_codes, v_codes, k_scale, v_scale, q, n_kv_heads, n_q_heads, head_dim,
                   sm_scale, rows)
 
@@ -330,8 +314,7 @@ def tree_prefill_attn_fp8kv(parent, tok_offset, n_tokens, leaf_node, k_codes, v_
     """Step-prefill attention over pools stored as E4M3 codes with one scale per pool or
     per kv head: the definition of tree_prefill_attn on K = k_scale[h] * value(k_codes),
     V = v_scale[h] * value(v_codes)."""
-    n_rows = int(prefill_q_ptr(n_tokens, leaf_node)[-1])
-    return _fp8kv(tree_prefill_attn, n_rows, parent, tok_offset, n_tokens, leaf_node, k_codes,
+    return _fp8kv(tree_prefill_attn, parent, tok_offset, n_tokens, leaf_node, k_codes,
                   v_codes, k_scale, v_scale, q, n_kv_heads, n_q_heads, head_dim, sm_scale, rows)
 
 

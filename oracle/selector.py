@@ -1,6 +1,6 @@
-"""CPU oracle of the ETS selection step (ETS paper Sec. 4.1-4.2, App. A): REBASE weights
-(Eq. 1 / Eq. 3) and the retained set that maximises the cost model (Eq. 4 / Eq. 5, as the
-ILP of App. A, Eq. 6 / Eq. 7), found by trying every non-empty set of leaves.
+"""CPU oracle of the ETS selection step (ETS paper Sec. 4.1-4.2, App. B): REBASE weights
+(Eq. 1 / Eq. 3) and the retained set that maximises the cost model (Eq. 2 / Eq. 4, as the
+ILPs of App. B, Eq. 6 / Eq. 7), found by trying every non-empty set of leaves.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ and by the benchmark's check; the product
 package never imports it and this module imports nothing from the product package.

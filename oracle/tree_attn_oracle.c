@@ -18,7 +18,8 @@
  *   LSE[l,j] = m + ln sum_t exp(s_t - m),  m = max_t s_t      (natural log)
  *   O[l,j,:] = sum_t exp(s_t - LSE) * V[t,h,:]
  *
- * all in fp64 after exact widening of the fp32 / bfloat16 inputs.  K[t,h,:] and
+ * all in fp64 after exact widening of the fp32 / bfloat16 inputs (fp64 inputs are taken
+ * as they are).  K[t,h,:] and
  * V[t,h,:] are D consecutive elements starting at element t * tok_stride +
  * h * head_stride of their pool, so that any memory order of (row, head) can be
  * described.  An empty
@@ -47,9 +48,12 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+/* element types of the inputs; ORACLE_F64 takes values that are already doubles (pools
+ * that a test dequantised itself from an 8-bit code and a scale) */
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F64 = 2 };
 
 static double load_elem(const void* base, int dtype, int64_t idx) {
+    if (dtype == ORACLE_F64) return ((const double*)base)[idx];
     if (dtype == ORACLE_F32) return (double)((const float*)base)[idx];
     uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16;
     float f;

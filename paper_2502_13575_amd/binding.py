@@ -39,7 +39,7 @@ class EtsStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "n_nodes", "live_nodes", "n_leaves", "unique_tokens", "flat_tokens", "unique_kv_bytes",
         "flat_kv_bytes", "n_segments", "n_partials", "n_stream_items", "n_cascade_items",
-        "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens")]
+        "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens", "shares_nodes")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -59,6 +59,15 @@ class EtsSelectInfo(C.Structure):
     _fields_ = [("objective", C.c_double), ("kept_nodes", C.c_int64), ("live_nodes", C.c_int64),
                 ("kept_clusters", C.c_int64), ("clusters", C.c_int64), ("bb_nodes", C.c_int64),
                 ("optimal", C.c_int32), ("pad", C.c_int32)]
+
+
+class EtsPlanCheckReport(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "decode_items", "prefill_items", "entry_table_entries", "max_entry_index",
+        "max_entry_overreach", "max_pool_row", "max_partial_row", "violations")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
 class EtsProfile(C.Structure):
@@ -116,6 +125,10 @@ def load_library():
     lib.ets_kv_append.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
     lib.ets_plan_advance.restype = C.c_int
     lib.ets_plan_advance.argtypes = [vp, vp, i32p]
+    lib.ets_plan_check.restype = C.c_int
+    lib.ets_plan_check.argtypes = [vp, C.POINTER(EtsPlanCheckReport)]
+    lib.ets_plan_append_rows.restype = C.c_int
+    lib.ets_plan_append_rows.argtypes = [vp, i64p]
     lib.ets_plan_prefill.restype = C.c_int
     lib.ets_plan_prefill.argtypes = [vp, C.POINTER(_EtsTree)]
     lib.ets_prefill_plan_stats.restype = C.c_int
@@ -131,6 +144,8 @@ def load_library():
     lib.ets_select_leaves.restype = C.c_int
     lib.ets_select_leaves.argtypes = [C.POINTER(_EtsTree), i32p, i32p, C.c_double, C.c_double,
                                       C.c_int64, C.POINTER(C.c_uint8), C.POINTER(EtsSelectInfo)]
+    lib.ets_bench_read_stream.restype = C.c_int
+    lib.ets_bench_read_stream.argtypes = [C.c_int, vp, C.c_int64, C.c_int, vp, C.c_int64, vp]
     lib.ets_profile_read.restype = C.c_int
     lib.ets_profile_read.argtypes = [vp, C.POINTER(EtsProfile)]
     lib.ets_strerror.restype = C.c_char_p
@@ -325,6 +340,22 @@ def ets_plan_advance(ctx, stream=None) -> bool:
     return bool(flag.value)
 
 
+def ets_plan_check(ctx) -> EtsPlanCheckReport:
+    """Raises EtsError when a kernel of the current plans would leave its tables."""
+    rep = EtsPlanCheckReport()
+    _check(load_library().ets_plan_check(ctx, C.byref(rep)), "ets_plan_check")
+    return rep
+
+
+def ets_plan_append_rows(ctx):
+    """int64 [L]: pool row that ets_kv_append writes for every leaf query now (-1: none)."""
+    st = ets_plan_stats(ctx)
+    rows = np.zeros(max(st.n_leaves, 1), dtype=np.int64)
+    _check(load_library().ets_plan_append_rows(ctx, rows.ctypes.data_as(C.POINTER(C.c_int64))),
+           "ets_plan_append_rows")
+    return rows[:st.n_leaves].copy()
+
+
 def ets_rebase_weights(rewards, budget: int, temperature: float):
     """int32 [n]: continuations per trajectory (ETS paper Eq. 1)."""
     r = np.ascontiguousarray(rewards, dtype=np.float64)
@@ -359,6 +390,14 @@ def ets_select_leaves(parent, leaf_node, weights, cluster=None, lambda_b=1.0, la
         float(lambda_d), int(node_limit), keep.ctypes.data_as(C.POINTER(C.c_uint8)),
         C.byref(info)), "ets_select_leaves")
     return keep[:leaf_node.shape[0]].astype(bool), info
+
+
+def ets_bench_read_stream(hip_device: int, buf, nbytes: int, nontemporal: bool, sink,
+                          sink_bytes: int, hip_stream=None):
+    stream = None if hip_stream is None else C.c_void_p(int(hip_stream))
+    _check(load_library().ets_bench_read_stream(int(hip_device), _dev_ptr(buf), int(nbytes),
+                                                int(bool(nontemporal)), _dev_ptr(sink),
+                                                int(sink_bytes), stream), "ets_bench_read_stream")
 
 
 def ets_profile_read(ctx) -> EtsProfile:
@@ -424,6 +463,12 @@ class Context:
 
     def plan_advance(self, stream=None) -> bool:
         return ets_plan_advance(self._ctx, stream)
+
+    def check(self) -> EtsPlanCheckReport:
+        return ets_plan_check(self._ctx)
+
+    def append_rows(self):
+        return ets_plan_append_rows(self._ctx)
 
     def profile_read(self) -> EtsProfile:
         return ets_profile_read(self._ctx)

@@ -29,18 +29,20 @@ __global__ void advance_runs_kernel(Run* __restrict__ runs, const AdvEntry* __re
 
 // One workgroup per growing node: for every kv head, head_bytes = head_dim * element
 // size (a multiple of 16) of K and of V go from row src[node] of k_new / v_new
-// ([leaf][kv head][head_dim]) to row row0[node] + advances of that head's plane of the
-// pool ([kv head][pool row][head_dim]).
+// ([leaf][kv head][head_dim]) to the node's newest row, last_row[node] + advances, of that
+// head's plane of the pool ([kv head][pool row][head_dim]).  A node that has no row yet
+// (negative entry) is skipped.
 __global__ __launch_bounds__(256) void kv_append_kernel(char* __restrict__ k_pool,
                                                         char* __restrict__ v_pool,
                                                         const char* __restrict__ k_new,
                                                         const char* __restrict__ v_new,
                                                         const int32_t* __restrict__ src,
-                                                        const int64_t* __restrict__ row0,
+                                                        const int64_t* __restrict__ last_row,
                                                         int advances, int n_kv_heads,
                                                         int head_bytes, int64_t pool_tokens) {
     const int node = blockIdx.x;
-    const int64_t row = row0[node] + advances;
+    const int64_t row = last_row[node] + advances;
+    if (row < 0) return;
     const int64_t from = (int64_t)src[node] * n_kv_heads * head_bytes;
     const int per_head = head_bytes / 16;
     const int pieces = n_kv_heads * per_head;

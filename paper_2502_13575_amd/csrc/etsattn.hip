@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "advance_kernel.hpp"
+#include "bench_kernels.hpp"
 #include "etsattn.h"
 #include "merge_kernel.hpp"
 #include "plan.h"
@@ -41,7 +42,7 @@ struct ets_ctx {
     int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
     AdvEntry* d_adv = nullptr;       // decode-step advance: tails to extend
     int32_t* d_adv_src = nullptr;    // per growing node: leaf query that supplies its new token
-    int64_t* d_adv_row0 = nullptr;   // per growing node: first free pool row at plan time
+    int64_t* d_adv_last_row = nullptr;  // per growing node: newest pool row at plan time
     // step prefill: its own plan and device tables
     PrefillPlan prefill;
     char* d_pre_buf = nullptr;
@@ -113,22 +114,32 @@ bool shape_supported(const ets_shape& s) {
     return g == 1 || g == 2 || g == 4 || g == 8;
 }
 
+ets_status upload_plan_unguarded(ets_ctx* c);
+
+// Copies the plan's index arrays to the device.  Nothing may throw across the C boundary:
+// a failed host allocation of the staging copy becomes a status code.
 ets_status upload_plan(ets_ctx* c) {
+    try {
+        return upload_plan_unguarded(c);
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+}
+
+ets_status upload_plan_unguarded(ets_ctx* c) {
     const Plan& p = c->plan;
     const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
     const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
-    // Every wave of a workgroup looks up the entries of "its" 16 query rows, also a wave
-    // whose row block lies past the item's last row (it computes nothing, but it fetches
-    // the query rows those entries name): with one query head per kv head that is up to
-    // kTreeAttnRowsPerItem entries from the item's first one, whatever the item's own
-    // count.  Both per-entry tables end in that many zero entries (leaf query 0, slot 0).
+    // Both per-entry tables end in kEntryPadding zero entries (leaf query 0, slot 0): a
+    // wave's 16-entry scalar load may run past the item's last entry (check_plan replays
+    // how far).
     const size_t b_ent =
-        align_up((p.ent_order.size() + kTreeAttnRowsPerItem) * sizeof(int32_t), 256);
+        align_up((p.ent_order.size() + kEntryPadding) * sizeof(int32_t), 256);
     const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
     const size_t b_adv = align_up(p.adv.size() * sizeof(AdvEntry), 256);
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
-    const size_t b_arow = align_up(p.adv_row0.size() * sizeof(int64_t), 256);
+    const size_t b_arow = align_up(p.adv_last_row.size() * sizeof(int64_t), 256);
     const size_t total =
         b_runs + b_stream + b_casc + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
 
@@ -150,7 +161,7 @@ ets_status upload_plan(ets_ctx* c) {
     const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
     const size_t o_adv = put(p.adv.data(), p.adv.size() * sizeof(AdvEntry), b_adv);
     const size_t o_asrc = put(p.adv_src.data(), p.adv_src.size() * sizeof(int32_t), b_asrc);
-    const size_t o_arow = put(p.adv_row0.data(), p.adv_row0.size() * sizeof(int64_t), b_arow);
+    const size_t o_arow = put(p.adv_last_row.data(), p.adv_last_row.size() * sizeof(int64_t), b_arow);
 
     DeviceGuard guard(c->device);
     if (!guard.ok) return ETS_ERR_HIP;
@@ -178,7 +189,7 @@ ets_status upload_plan(ets_ctx* c) {
     c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
     c->d_adv = reinterpret_cast<AdvEntry*>(c->d_buf + o_adv);
     c->d_adv_src = reinterpret_cast<int32_t*>(c->d_buf + o_asrc);
-    c->d_adv_row0 = reinterpret_cast<int64_t*>(c->d_buf + o_arow);
+    c->d_adv_last_row = reinterpret_cast<int64_t*>(c->d_buf + o_arow);
     return ETS_OK;
 }
 
@@ -240,7 +251,17 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     }
 }
 
+ets_status upload_prefill_plan_unguarded(ets_ctx* c);
+
 ets_status upload_prefill_plan(ets_ctx* c) {
+    try {
+        return upload_prefill_plan_unguarded(c);
+    } catch (const std::bad_alloc&) {
+        return ETS_ERR_NOMEM;
+    }
+}
+
+ets_status upload_prefill_plan_unguarded(ets_ctx* c) {
     const PrefillPlan& p = c->prefill;
     // the kernel's prologue reads a whole descriptor per thread only below n_runs, but
     // keep the table padded so that a wide scalar load near its end stays inside
@@ -287,7 +308,13 @@ void mark(ets_ctx* c, int which, hipStream_t stream) {
             c->profile = false;
             return;
         }
-        c->events.push_back(e);
+        try {
+            c->events.push_back(e);
+        } catch (const std::bad_alloc&) {
+            (void)hipEventDestroy(e);
+            c->profile = false;
+            return;
+        }
     }
     (void)hipEventRecord(c->events[idx], stream);
 }
@@ -440,6 +467,7 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
         ctx->opt.cascade_rows = value;
     } else if (!std::strcmp(key, "wave_items")) ctx->opt.wave_items = value;
     else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
+    else if (!std::strcmp(key, "require_sharing")) ctx->opt.require_sharing = value != 0;
     else if (!std::strcmp(key, "out_bf16")) ctx->out_bf16 = value != 0;
     else if (!std::strcmp(key, "profile")) {
         if (value != 0 && ctx->device < 0) return ETS_ERR_HIP;
@@ -550,10 +578,11 @@ ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_
     const int n = (int)p.adv_node.size();
     if (n == 0) return ETS_OK;
     if (!k_pool || !v_pool || !k_new || !v_new) return ETS_ERR_INVALID_ARG;
-    // every growing node's next row has to exist in the pool
+    // the newest row of every growing node has to exist in the pool
     int64_t last_row = -1;
-    for (const int64_t r0 : p.adv_row0) last_row = std::max(last_row, r0 + p.advances);
+    for (const int64_t r0 : p.adv_last_row) last_row = std::max(last_row, r0 + p.advances);
     if (last_row >= pool_tokens) return ETS_ERR_INVALID_ARG;
+    if (last_row < 0) return ETS_OK;  // no growing node has a row
     const int64_t esz =
         ctx->kv_format == ETS_KV_FP8_E4M3 ? 1 : ctx->shape.dtype == ETS_F32 ? 4 : 2;
     const int head_bytes = (int)(ctx->shape.head_dim * esz);
@@ -563,11 +592,51 @@ ets_status ets_kv_append(ets_ctx* ctx, void* k_pool, void* v_pool, int64_t pool_
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)n), dim3(256), 0, stream,
                        static_cast<char*>(k_pool), static_cast<char*>(v_pool),
                        static_cast<const char*>(k_new), static_cast<const char*>(v_new),
-                       ctx->d_adv_src, ctx->d_adv_row0, (int)p.advances, ctx->shape.n_kv_heads,
+                       ctx->d_adv_src, ctx->d_adv_last_row, (int)p.advances, ctx->shape.n_kv_heads,
                        head_bytes, pool_tokens);
     if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
     ctx->last_stream = stream;
     ctx->stream_used = true;
+    return ETS_OK;
+}
+
+ets_status ets_plan_check(const ets_ctx* ctx, ets_plan_check_report* report) {
+    if (!ctx) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid && !ctx->prefill.valid) return ETS_ERR_NO_PLAN;
+    ets_plan_check_report rep{};
+    rep.max_entry_index = rep.max_pool_row = rep.max_partial_row = -1;
+    bool ok = true;
+    if (ctx->plan.valid) {
+        PlanCheck c;
+        ok = check_plan(ctx->plan, ctx->shape, c) && ok;
+        rep.decode_items = c.items;
+        rep.entry_table_entries = c.entry_table_entries;
+        rep.max_entry_index = c.max_entry_index;
+        rep.max_entry_overreach = c.max_entry_overreach;
+        rep.max_pool_row = c.max_pool_row;
+        rep.max_partial_row = c.max_partial_row;
+        rep.violations += c.violations;
+    }
+    if (ctx->prefill.valid) {
+        PlanCheck c;
+        ok = check_prefill_plan(ctx->prefill, ctx->shape, c) && ok;
+        rep.prefill_items = c.items;
+        rep.max_pool_row = std::max(rep.max_pool_row, c.max_pool_row);
+        rep.violations += c.violations;
+    }
+    if (report) *report = rep;
+    return ok ? ETS_OK : ETS_ERR_BAD_TREE;
+}
+
+ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows) {
+    if (!ctx || !rows) return ETS_ERR_INVALID_ARG;
+    if (!ctx->plan.valid) return ETS_ERR_NO_PLAN;
+    const Plan& p = ctx->plan;
+    for (int64_t l = 0; l < p.stats.n_leaves; ++l) rows[l] = -1;
+    for (size_t i = 0; i < p.adv_node.size(); ++i) {
+        const int64_t row = p.adv_last_row[i] + p.advances;
+        rows[p.adv_src[i]] = row < 0 ? -1 : row;
+    }
     return ETS_OK;
 }
 
@@ -765,6 +834,31 @@ ets_status ets_select_leaves(const ets_tree* tree, const int32_t* weights, const
         info->optimal = r.optimal ? 1 : 0;
         info->pad = 0;
     }
+    return ETS_OK;
+}
+
+ets_status ets_bench_read_stream(int hip_device, const void* buf, int64_t bytes, int nontemporal,
+                                 void* sink, int64_t sink_bytes, void* hip_stream) {
+    if (hip_device < 0 || !buf || !sink || bytes < 0 || misaligned(buf) ||
+        (reinterpret_cast<uintptr_t>(sink) & 3u))
+        return ETS_ERR_INVALID_ARG;
+    DeviceGuard guard(hip_device);
+    if (!guard.ok) return ETS_ERR_HIP;
+    // enough workgroups to fill every compute unit several times over, each with many spans
+    const int64_t spans = bytes / 16 / (256 * 8);
+    const int64_t grid = std::max<int64_t>(1, std::min<int64_t>(spans, 256 * 16));
+    if (sink_bytes < grid * 4) return ETS_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    (void)hipGetLastError();
+    if (nontemporal)
+        hipLaunchKernelGGL(read_stream_kernel<true>, dim3((unsigned)grid), dim3(256), 0, stream,
+                           static_cast<const bench_u32x4_t*>(buf), bytes / 16,
+                           static_cast<uint32_t*>(sink));
+    else
+        hipLaunchKernelGGL(read_stream_kernel<false>, dim3((unsigned)grid), dim3(256), 0, stream,
+                           static_cast<const bench_u32x4_t*>(buf), bytes / 16,
+                           static_cast<uint32_t*>(sink));
+    if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
     return ETS_OK;
 }
 

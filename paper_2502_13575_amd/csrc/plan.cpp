@@ -31,7 +31,7 @@ struct Chunk {
     int32_t run_begin, run_end, tokens;
 };
 
-constexpr int64_t kMaxPiecesPerChunk = 256;  // step list the matrix-core kernel keeps in LDS
+constexpr int64_t kMaxPiecesPerChunk = kTreeAttnMaxSteps;  // step list the kernel keeps in LDS
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
@@ -235,6 +235,8 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // shared when the KV bytes this saves exceed the partial bytes it adds.
     const bool use_mfma = opt.mfma != 0 && shape.dtype == ETS_BF16 && shape.head_dim == 128;
     const bool cascade_ok = mode == ETS_PLAN_TREE && use_mfma && opt.cascade_min_leaves > 0;
+    if (mode == ETS_PLAN_TREE && opt.require_sharing && !cascade_ok) return ETS_ERR_UNSUPPORTED;
+    st.shares_nodes = cascade_ok ? 1 : 0;
     const int64_t piece = use_mfma ? 32 : 0;
     p.piece = (int32_t)piece;
     auto grow_end_of = [&](int32_t node) { return p.tok_offset[node] + p.n_tokens[node]; };
@@ -398,14 +400,14 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         std::vector<int32_t> first(N, -1);
         p.adv_node.clear();
         p.adv_src.clear();
-        p.adv_row0.clear();
+        p.adv_last_row.clear();
         for (int32_t l = 0; l < L; ++l) {
             const int32_t n = p.leaf_node[l];
             if (first[n] >= 0) continue;
             first[n] = l;
             p.adv_node.push_back(n);
             p.adv_src.push_back(l);
-            p.adv_row0.push_back(grow_end_of(n));
+            p.adv_last_row.push_back(p.n_tokens[n] > 0 ? grow_end_of(n) - 1 : kNoRow);
         }
         p.adv_room = piece > 0 ? 32 : std::numeric_limits<int32_t>::max();
     }
@@ -478,6 +480,87 @@ ets_status build_plan(const ets_shape& shape, const PlanOptions& opt, const ets_
         plan.valid = false;
         return ETS_ERR_NOMEM;
     }
+}
+
+bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
+    out = PlanCheck{};
+    const int64_t L = (int64_t)p.leaf_node.size();
+    const int G = shape.n_q_heads / shape.n_kv_heads;
+    const int per_block = std::max(1, 16 / G);  // entries whose rows make up a 16-row block
+    const int64_t n_runs = (int64_t)p.runs.size();
+    out.entry_table_entries = (int64_t)p.ent_order.size() + kEntryPadding;
+    auto bad = [&](bool cond) {
+        if (cond) out.violations += 1;
+    };
+    auto entry_leaf = [&](int64_t idx) -> int64_t {  // padding entries hold zero
+        return idx < (int64_t)p.ent_order.size() ? p.ent_order[(size_t)idx] : 0;
+    };
+    bad(p.ent_base.size() != p.ent_order.size());
+    for (size_t i = 0; i < p.cascade_items.size(); ++i) {
+        const CascadeItem& it = p.cascade_items[i];
+        const bool wave_item = (int64_t)i >= p.n_single;
+        out.items += 1;
+        // the step list
+        bad(it.run_begin < 0 || it.run_end < it.run_begin || it.run_end > n_runs);
+        if (!wave_item) bad(it.run_end - it.run_begin > kTreeAttnMaxSteps);
+        for (int64_t r = it.run_begin; r < it.run_end && r < n_runs; ++r) {
+            const Run& run = p.runs[(size_t)r];
+            bad(run.n < 0 || run.n > 32 || run.tok < 0);
+            if (run.n > 0) {
+                bad(run.tok + run.n > p.stats.min_pool_tokens);
+                out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+        // the entries: every wave loads 16 consecutive entries from its block's first one
+        const int64_t R = (int64_t)it.n_ent * G;
+        bad(it.n_ent < 1 || R > kTreeAttnRowsPerItem || it.ent_begin < 0 ||
+            (int64_t)it.ent_begin + it.n_ent > L);
+        if (wave_item) bad(R > 16);
+        const bool rowpar = R > 16;
+        const int n_blocks = (int)((R + 15) / 16);
+        for (int w = 0; w < 4; ++w) {
+            const int blk = rowpar && w < n_blocks ? w : 0;
+            const int64_t first = (int64_t)it.ent_begin + (16 * blk) / G;
+            const int64_t last_loaded = first + 15;
+            out.max_entry_index = std::max(out.max_entry_index, last_loaded);
+            out.max_entry_overreach = std::max(
+                out.max_entry_overreach, last_loaded - ((int64_t)it.ent_begin + it.n_ent - 1));
+            bad(last_loaded >= out.entry_table_entries);
+            // the entries whose query rows the wave fetches (rows past R included)
+            for (int k = 0; k < per_block; ++k) {
+                const int64_t leaf = entry_leaf(first + k);
+                bad(leaf < 0 || leaf >= std::max<int64_t>(L, 1));
+            }
+            if (wave_item) break;  // one wave walks the item
+        }
+        // the partial rows it writes
+        for (int32_t e = 0; e < it.n_ent && (int64_t)it.ent_begin + e < L; ++e) {
+            const int32_t leaf = p.ent_order[(size_t)(it.ent_begin + e)];
+            const int64_t slot = (int64_t)p.part_base[(size_t)leaf] + it.slot_off;
+            bad(it.slot_off < 0 || slot >= p.part_base[(size_t)leaf + 1]);
+            out.max_partial_row =
+                std::max(out.max_partial_row, slot * shape.n_q_heads + shape.n_q_heads - 1);
+        }
+    }
+    for (const StreamItem& it : p.stream_items) {
+        out.items += 1;
+        bad(it.run_begin < 0 || it.run_end < it.run_begin || it.run_end > n_runs);
+        bad(it.entry < 0 || it.entry >= L);
+        if (it.entry >= 0 && it.entry < L)
+            bad(it.slot < p.part_base[(size_t)it.entry] || it.slot >= p.part_base[(size_t)it.entry + 1]);
+        out.max_partial_row = std::max(
+            out.max_partial_row, (int64_t)it.slot * shape.n_q_heads + shape.n_q_heads - 1);
+        for (int64_t r = it.run_begin; r < it.run_end && r < n_runs; ++r) {
+            const Run& run = p.runs[(size_t)r];
+            bad(run.n < 0 || run.tok < 0);
+            if (run.n > 0) {
+                bad(run.tok + run.n > p.stats.min_pool_tokens);
+                out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+    }
+    bad(out.max_partial_row >= p.stats.n_partials * shape.n_q_heads);
+    return out.violations == 0;
 }
 
 bool leaf_cover(const Plan& plan, int32_t leaf, std::vector<int64_t>& rows,

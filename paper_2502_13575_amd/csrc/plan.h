@@ -55,6 +55,17 @@ struct AdvEntry {
     int32_t pad;
 };
 
+// Geometry of the matrix-core kernel that the planner and the launch code rely on.
+constexpr int kTreeAttnRowsPerItem = 64;  // query rows one work item serves at most
+constexpr int kTreeAttnMaxSteps = 256;    // steps per work item that takes a workgroup
+// Both per-entry tables (ent_order, ent_base) end in this many zero entries on the device:
+// a wave fetches the entries of its 16 query rows with one 16-entry scalar load, which may
+// run up to 15 entries past the item's last entry (see check_plan).
+constexpr int kEntryPadding = 64;
+
+// adv_last_row of a node that has no row yet; stays negative under any number of advances
+constexpr int64_t kNoRow = -(int64_t(1) << 62);
+
 struct PlanOptions {
     int64_t kv_elem_bytes = 0;       // bytes per pool element; 0 = by the shape's dtype
     int64_t stream_chunk = 0;        // 0 = auto
@@ -64,6 +75,7 @@ struct PlanOptions {
                                      // walked by one wave, four such items to a workgroup (0 = off)
     int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
+    int64_t require_sharing = 0;     // 1 = a tree-mode plan that cannot share nodes is refused
 };
 
 struct Plan {
@@ -87,7 +99,8 @@ struct Plan {
     std::vector<AdvEntry> adv;        // tails to extend
     std::vector<int32_t> adv_node;    // distinct leaf nodes, in order of first appearance
     std::vector<int32_t> adv_src;     // first leaf query of that node (supplies the new token)
-    std::vector<int64_t> adv_row0;    // first free pool row of that node at plan time
+    std::vector<int64_t> adv_last_row;  // newest pool row of that node at plan time (kNoRow: none);
+                                        // after a advances in place it is this + a
     bool adv_in_place = false;        // every tail has a record (else advancing re-plans)
     int32_t adv_room = 0;             // advances the spare runs still hold
     int32_t advances = 0;             // advances applied in place since the plan was built
@@ -108,6 +121,21 @@ ets_status build_plan(const ets_shape& shape, const PlanOptions& opt, const ets_
 
 // Root->leaf chain of leaf query `leaf` (node ids), appended to `out`.
 void chain_of(const Plan& plan, int32_t leaf, std::vector<int32_t>& out);
+
+// What the kernels will touch, replayed on the host from the tables they read: the
+// highest index into the per-entry tables any wave loads, the leaf queries whose q rows it
+// fetches, the partial rows it writes, the pool rows its steps name.
+struct PlanCheck {
+    int64_t items = 0;
+    int64_t entry_table_entries = 0;  // entries of each table on the device, padding included
+    int64_t max_entry_index = -1;     // highest entry index loaded
+    int64_t max_entry_overreach = 0;  // entries loaded past an item's own last entry, at most
+    int64_t max_pool_row = -1;        // highest pool row named by a step
+    int64_t max_partial_row = -1;     // highest (slot, head) row written
+    int64_t violations = 0;
+};
+// Returns true when every access stays inside its table / the pool / the workspace.
+bool check_plan(const Plan& plan, const ets_shape& shape, PlanCheck& out);
 
 // Rows read for `leaf` according to the work items, ordered by partial slot.
 // Returns false if a slot of the leaf is produced twice or never.

@@ -203,4 +203,30 @@ bool prefill_cover(const PrefillPlan& p, int32_t leaf, int32_t tok, std::vector<
     return false;
 }
 
+bool check_prefill_plan(const PrefillPlan& p, const ets_shape& shape, PlanCheck& out) {
+    out = PlanCheck{};
+    const int G = shape.n_q_heads / shape.n_kv_heads;
+    const int64_t n_runs = (int64_t)p.runs.size();
+    auto bad = [&](bool cond) {
+        if (cond) out.violations += 1;
+    };
+    for (const PrefillItem& it : p.items) {
+        out.items += 1;
+        bad(it.run_begin < 0 || it.run_end < it.run_begin || it.run_end > n_runs);
+        bad(it.n_tok < 1 || it.n_tok * G > kPrefillRowsPerItem);
+        bad(it.leaf < 0 || it.leaf >= p.stats.n_leaves);
+        // query tokens past n_tok are clamped to the block's last one by the kernel
+        bad(it.q_row0 < 0 || it.q_row0 + it.n_tok > p.stats.n_q_rows);
+        for (int64_t r = it.run_begin; r < it.run_end && r < n_runs; ++r) {
+            const Run& run = p.runs[(size_t)r];
+            bad(run.n < 0 || run.n > 32 || run.tok < 0);
+            if (run.n > 0) {
+                bad(run.tok + run.n > p.stats.min_pool_tokens);
+                out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+    }
+    return out.violations == 0;
+}
+
 }  // namespace ets

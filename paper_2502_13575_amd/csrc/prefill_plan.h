@@ -53,4 +53,9 @@ ets_status build_prefill_plan(const ets_shape& shape, const ets_tree& tree, Pref
 // Returns false if no item holds that token.
 bool prefill_cover(const PrefillPlan& plan, int32_t leaf, int32_t tok, std::vector<int64_t>& rows);
 
+// Replays what the prefill kernel reads and writes from its tables (run lists against the
+// pool, query and output rows against n_q_rows); true when everything is in bounds.
+// Only items, max_pool_row and violations of `out` are filled.
+bool check_prefill_plan(const PrefillPlan& plan, const ets_shape& shape, PlanCheck& out);
+
 }  // namespace ets

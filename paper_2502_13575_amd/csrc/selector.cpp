@@ -1,4 +1,4 @@
-// Exact solver of the ETS cost model (paper App. A, Eq. 7).
+// Exact solver of the ETS cost model (ETS paper Sec. 4.2, Eq. 4; as an ILP: App. B, Eq. 7).
 //
 // Without the coverage term the problem decomposes over the tree: a leaf is worth
 // a_i = W_i / sum W - c with c = lambda_b / |V_A|, an inner node costs c as soon as a leaf

@@ -1,7 +1,7 @@
-// The ETS selection step on the host (ETS paper Sec. 4.1-4.2, App. A): REBASE weights
+// The ETS selection step on the host (ETS paper Sec. 4.1-4.2, App. B): REBASE weights
 // (Eq. 1 / Eq. 3) and the set of leaves that maximises the cost model
 //   sum_{i in S} W_i / sum_i W_i  -  lambda_b |V_S| / |V_A|  +  lambda_d |C_S| / |C_A|
-// (Eq. 5; the ILP of Eq. 7), solved exactly: a tree recursion gives the optimum for the
+// (Eq. 2 without and Eq. 4 with the coverage term; as ILPs Eq. 6 and Eq. 7 of App. B), solved exactly: a tree recursion gives the optimum for the
 // budget term, the coverage term is handled by branch and bound over the clusters.
 #pragma once
 

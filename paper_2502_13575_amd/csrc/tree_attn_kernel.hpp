@@ -106,8 +106,7 @@ __device__ __forceinline__ std::conditional_t<FP8, u32x2_t, u32x4_t> load_row_pi
         return __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2));
 }
 
-constexpr int kTreeAttnRowsPerItem = 64;  // 4 waves x 16 rows
-constexpr int kTreeAttnMaxSteps = 256;    // steps per work item (planner's cap)
+static_assert(kTreeAttnRowsPerItem == 64, "4 waves x 16 rows");
 constexpr int kTreeAttnKRow = 17;         // 16-byte units per padded K row in LDS (272 bytes)
 
 // One step of a row-parallel item: 32 staged tokens (V already fp16) against one block
@@ -258,9 +257,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int R = it.n_ent << g_shift;
     const bool rowpar = R > 16;
     const int n_blocks = (R + 15) >> 4;
-    // the row block this wave computes: block w when row parallel, block 0 otherwise
-    const int blk = rowpar ? w : 0;
+    // the row block this wave computes: block w when row parallel, block 0 otherwise.  A
+    // row-parallel wave past the item's last block computes nothing; it looks up (and
+    // fetches the query rows of) block 0 instead of entries that are not the item's.
     const bool computes = w < n_blocks;  // row parallel only; token parallel: every wave
+    const int blk = rowpar && computes ? w : 0;
     // a token-parallel wave needs its half of a step only if the step reaches it
     const int load_min = rowpar ? 0 : 16 * hw;
     const int n_steps = it.run_end - it.run_begin;
@@ -313,9 +314,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // order): the lane's query index, the first tile, the step list, then the query
     // row, which depends on the first.
     // The leaf queries of the wave's 16 rows and their partial slots come through scalar
-    // loads (uniform addresses; both tables are padded, so entries past the item's own
-    // are readable): scalar loads do not queue behind the CU's K/V loads, and the query
-    // rows can be requested one memory round trip earlier.
+    // loads (uniform addresses; a 16-entry load may run up to 15 entries past the item's
+    // own, which is what the tables' zero padding is for: those name leaf query 0 or a
+    // neighbouring item's leaf queries, whose rows are read and never written): scalar
+    // loads do not queue behind the CU's K/V loads, and the query rows can be requested
+    // one memory round trip earlier.
     const int r_lane = 16 * blk + a;
     const int e_lane = a >> g_shift;  // entry of the lane's row within the wave's block
     const int32_t* s_ent = ent_order + it.ent_begin + ((16 * blk) >> g_shift);

@@ -121,8 +121,8 @@ def test_fp8kv_decode_loop_appends_codes():
             kn = finite[r.integers(0, finite.size, size=(tree.n_leaves, cfg.n_kv_heads, 128))]
             vn = finite[r.integers(0, finite.size, size=(tree.n_leaves, cfg.n_kv_heads, 128))]
             n_tokens = oracle.append_kv(tree.tok_offset, n_tokens, tree.leaf_node, kc, vc, kn, vn)
-            ctx.kv_append(kd, vd, tree.pool_tokens, to_device(kn), to_device(vn))
             ctx.plan_advance()
+            ctx.kv_append(kd, vd, tree.pool_tokens, to_device(kn), to_device(vn))
             out, lse, _ = run(ctx, tree, kd, vd, qd, plan=False)
             if step % 7 == 0 or step >= steps - 2:
                 grown = type(tree)(tree.parent, tree.tok_offset, n_tokens, tree.leaf_node,

@@ -260,6 +260,140 @@ def test_plan_advance_fuzz_and_duplicates():
                     _check_cover(ctx, t, n_tokens)
 
 
+_CHECK_SHAPES = [(2, 8, 128, ets.ETS_BF16), (4, 4, 128, ets.ETS_BF16), (2, 4, 128, ets.ETS_BF16),
+                 (1, 1, 128, ets.ETS_BF16), (2, 16, 128, ets.ETS_BF16), (1, 8, 64, ets.ETS_BF16),
+                 (2, 2, 64, ets.ETS_F32)]
+
+
+def test_plan_check_replays_kernel_accesses_on_configs():
+    """ets_plan_check walks the tables the kernels read: on every configuration every step
+    stays inside the pool, every partial row inside the workspace, and no wavefront loads
+    an entry further than 15 past its item's last one (one 16-entry scalar load), which the
+    tables' padding covers."""
+    for name, cfg in CONFIGS.items():
+        t = make_tree(cfg)
+        with _ctx(cfg) as ctx:
+            st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            if cfg.dtype == "bf16" and cfg.head_dim == 128:
+                ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            rep = ctx.check()
+            assert rep.violations == 0, name
+            assert rep.decode_items == st.n_cascade_items + st.n_stream_items
+            assert rep.max_pool_row == st.min_pool_tokens - 1
+            assert rep.max_partial_row == st.n_partials * cfg.n_q_heads - 1
+            assert rep.max_entry_overreach <= 15
+            assert rep.max_entry_index < rep.entry_table_entries
+            assert rep.entry_table_entries >= t.n_leaves + 16
+
+
+def test_plan_check_sweep_of_random_forests():
+    """The sweep that once found a wavefront reading entries of the next table (one query
+    head per kv head, row blocks past an item's last row): 3000 random forests over the
+    head geometries, planner knobs, both plan modes, decode-step advances and the prefill
+    plan; every replay stays in bounds with at most 15 entries of overreach."""
+    from workload import with_growth_room
+    worst = 0
+    for seed in range(20000, 23000):
+        r = np.random.default_rng(seed)
+        t = random_tree(seed, n_nodes=int(r.integers(1, 140)), n_leaves=int(r.integers(1, 90)),
+                        max_tokens=int(r.choice([1, 5, 33, 70, 300, 2000])),
+                        p_root=float(r.choice([0.02, 0.1, 0.5])),
+                        p_empty=float(r.choice([0.0, 0.15, 0.6])))
+        shape = _CHECK_SHAPES[seed % len(_CHECK_SHAPES)]
+        opts = {"stream_chunk": int(r.choice([0, 32, 64, 1000])),
+                "cascade_chunk": int(r.choice([0, 32, 96, 1000])),
+                "cascade_rows": int(r.choice([64, 16, 32])),
+                "wave_items": int(r.choice([512, 0, 48, 100000])),
+                "cascade_min_leaves": int(r.choice([2, 0, 3, 9])),
+                "mfma": int(r.choice([1, 1, 0]))}
+        mode = int(r.choice([0, 0, 1]))
+        if seed % 3 == 0:
+            t = with_growth_room(t, 40)
+        with _ctx(shape) as ctx:
+            for k, v in opts.items():
+                ctx.set_option(k, v)
+            ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, mode)
+            if seed % 4 == 0 and shape[2] == 128 and shape[3] == ets.ETS_BF16:
+                ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            rep = ctx.check()
+            assert rep.violations == 0 and rep.max_entry_overreach <= 15, (seed, rep.as_dict())
+            worst = max(worst, rep.max_entry_overreach)
+            if seed % 3 == 0:
+                for step in range(int(r.choice([1, 34]))):
+                    ctx.plan_advance()
+                rep = ctx.check()
+                assert rep.violations == 0 and rep.max_entry_overreach <= 15, (seed, rep.as_dict())
+    assert worst == 15  # the sweep does reach the furthest load the kernel makes
+
+
+def test_shapes_without_node_sharing_say_so_or_refuse():
+    """Shared nodes are read once only for bf16 pools with head_dim 128.  Other accepted
+    shapes fall back to per-leaf reads and report it (shares_nodes 0, nothing on the
+    shared-node kernel); with "require_sharing" the tree-mode plan is refused instead."""
+    t = make_tree(CONFIGS["c2_w16"])
+    for shape, shares in [((8, 32, 128, ets.ETS_BF16), 1), ((8, 32, 64, ets.ETS_BF16), 0),
+                          ((8, 32, 128, ets.ETS_F32), 0), ((1, 2, 64, ets.ETS_F32), 0)]:
+        with _ctx(shape) as ctx:
+            st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            assert st.shares_nodes == shares
+            assert (st.cascade_tokens > 0) == bool(shares)
+            if not shares:
+                assert st.stream_tokens == st.flat_tokens
+            assert ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node,
+                            ets.ETS_PLAN_FLAT).shares_nodes == 0
+            ctx.set_option("require_sharing", 1)
+            if shares:
+                assert ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node).shares_nodes == 1
+            else:
+                with pytest.raises(ets.EtsError) as e:
+                    ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+                assert e.value.status == 4  # ETS_ERR_UNSUPPORTED
+            # the flat baseline is a per-leaf plan by definition and stays available
+            ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, ets.ETS_PLAN_FLAT)
+    with _ctx((8, 32, 128, ets.ETS_BF16)) as ctx:
+        ctx.set_option("require_sharing", 1)
+        ctx.set_option("mfma", 0)
+        with pytest.raises(ets.EtsError) as e:
+            ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert e.value.status == 4
+
+
+def test_append_rows_follow_the_grown_tree_whatever_the_layer_count():
+    """ets_kv_append writes the newest row of every distinct leaf node as the plan counts it:
+    after a advances that is row tok_offset + n_tokens0 + a - 1, the row the oracle's
+    append_kv (the definition) fills on its a-th call -- through the in-place advances and
+    through the re-plan, for the first leaf query of every node only."""
+    import oracle
+    from workload import with_growth_room
+    for seed in range(4):
+        t = with_growth_room(random_tree(300 + seed, 30, 10, 40), 45)
+        first = {}
+        for l, n in enumerate(t.leaf_node.tolist()):
+            first.setdefault(n, l)
+        with _ctx((2, 8, 128, ets.ETS_BF16)) as ctx:
+            ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+            # a plan that was just built: the last row the tree names (none for an empty node)
+            rows = ctx.append_rows()
+            for l, n in enumerate(t.leaf_node.tolist()):
+                want = t.tok_offset[n] + t.n_tokens[n] - 1 if first[n] == l and t.n_tokens[n] > 0 else -1
+                assert rows[l] == want, (seed, l)
+            # the oracle's append marks, in a pool of zeros, the row every call fills
+            n_tokens = t.n_tokens.copy()
+            pool = np.zeros((t.pool_tokens + 64, 1, 1), dtype=np.int64)
+            for a in range(1, 41):
+                ctx.plan_advance()
+                marks = np.arange(1, t.n_leaves + 1, dtype=np.int64).reshape(-1, 1, 1) + 1000 * a
+                n_tokens = oracle.append_kv(t.tok_offset, n_tokens, t.leaf_node, pool, pool.copy(),
+                                            marks, marks)
+                rows = ctx.append_rows()
+                assert np.array_equal(rows, ctx.append_rows())  # asking twice changes nothing
+                for l, n in enumerate(t.leaf_node.tolist()):
+                    if first[n] == l:
+                        assert pool[rows[l], 0, 0] == 1000 * a + l + 1, (seed, a, l)
+                    else:
+                        assert rows[l] == -1
+
+
 def test_advance_and_append_error_paths():
     with _ctx((2, 8, 128, ets.ETS_BF16)) as ctx:
         with pytest.raises(ets.EtsError) as e:

@@ -24,10 +24,8 @@ def _both_entry_points(ctx, cfg, tree, seed_note):
     ws = torch.empty(st.workspace_bytes, dtype=torch.uint8, device="cuda:0")
     ctx.decode(kd, vd, tree.pool_tokens, qd, out_a, lse_a, ws, ws.numel())
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
     ctx.decode_static(kd, vd, tree.pool_tokens, qd, out_b, lse_b)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
     # same kernels, same partial slots: the two entry points agree bit for bit
     assert torch.equal(out_a, out_b), seed_note
     assert torch.equal(lse_a, lse_b), seed_note

@@ -8,7 +8,7 @@ Per search step: every kept leaf i receives W_i continuations (REBASE weights, E
 the new nodes get a step length, a reward near their parent's and a cluster label (a few
 "phrasings" per parent: siblings are often redundant).  Policy "rebase" continues from
 every leaf with a weight; policy "ets" first keeps the set that maximises the cost model
-(Eq. 5 / Eq. 7) and re-weights the kept leaves (Eq. 3).
+(Eq. 4; App. B, Eq. 7) and re-weights the kept leaves (Eq. 3).
 """
 from __future__ import annotations
 
