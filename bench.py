@@ -315,6 +315,8 @@ def main():
     # measures its own spacing)
     kernel_us = {"stream_attn": round(prof.stream_ms / max(prof.calls, 1) * 1e3, 2)
                  if st.n_stream_items > 0 else 0.0,
+                 "wide_attn": round(prof.wide_ms / max(prof.calls, 1) * 1e3, 2)
+                 if st.n_wide_items > 0 else 0.0,
                  "tree_attn": round(prof.cascade_ms / max(prof.calls, 1) * 1e3, 2),
                  "merge": round(prof.merge_ms / max(prof.calls, 1) * 1e3, 2)}
     log("tree: %.3f ms/step, %.0f leaf-queries/s, unique-KV %.0f GB/s (%.1f%% of peak); "

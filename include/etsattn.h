@@ -120,6 +120,8 @@ typedef struct {
     int64_t stream_tokens;   /* tokens read by the streaming kernel, repeats included    */
     int64_t shares_nodes;    /* 1: shared nodes are read once per call (bf16, head_dim   */
                              /* 128, tree mode); 0: every leaf reads its chain itself    */
+    int64_t n_wide_items;    /* work items of the kernel for widely shared segments      */
+    int64_t wide_tokens;     /* unique tokens of those segments (part of cascade_tokens) */
 } ets_stats;
 
 typedef enum {
@@ -234,6 +236,14 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *                    work item of a shared segment serves: 16, 32 or 64
  *                    (default 64); a segment with more rows is read by several
  *                    items
+ *   "wide_rows"      a shared segment with more query rows than this is read by the
+ *                    wide kernel (256 query rows per work item, bound by the matrix
+ *                    cores) instead of by several items of "cascade_rows" rows each
+ *                    (0 = never; -1, the default = by the head geometry: 64 with 8 query
+ *                    heads per kv head, where it measures 5 % faster on a batch of
+ *                    searches, never with fewer, where items of 64 rows are as fast)
+ *   "interleave"     1 (default) = the workgroups that hold small items are spread through
+ *                    the launch order; 0 = they follow all the others
  *   "wave_items"     a work item of at most 16 query rows and at most this many
  *                    tokens is walked by a single wavefront, four such items to
  *                    a workgroup (default 512; 0 = every item gets a workgroup)
@@ -249,7 +259,7 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *                    projection's input in bf16; 0 (default) = fp32.  Effective from
  *                    the next decode call; lse stays fp32
  *   "profile"        1 = record kernel times (see ets_profile_read), 0 = off
- * Unknown key or negative value: ETS_ERR_INVALID_ARG. */
+ * Unknown key or negative value (other than wide_rows = -1): ETS_ERR_INVALID_ARG. */
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 
 /* Storage format of the K/V pools.  The search is bound by the bytes of KV state that
@@ -330,9 +340,10 @@ ets_status ets_tree_decode_attn_static(ets_ctx* ctx, const void* k_pool, const v
  * returns the summed kernel times since the previous read and clears them. */
 typedef struct {
     int64_t calls;
-    double stream_ms;  /* per-leaf streaming kernel  */
-    double cascade_ms; /* shared-node kernel         */
-    double merge_ms;   /* log-sum-exp merge kernel   */
+    double stream_ms;  /* per-leaf streaming kernel                  */
+    double cascade_ms; /* shared-node kernel                         */
+    double merge_ms;   /* log-sum-exp merge kernel                   */
+    double wide_ms;    /* kernel for widely shared segments          */
 } ets_profile;
 ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out /* host */);
 

@@ -39,7 +39,8 @@ class EtsStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "n_nodes", "live_nodes", "n_leaves", "unique_tokens", "flat_tokens", "unique_kv_bytes",
         "flat_kv_bytes", "n_segments", "n_partials", "n_stream_items", "n_cascade_items",
-        "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens", "shares_nodes")]
+        "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens", "shares_nodes",
+        "n_wide_items", "wide_tokens")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -72,7 +73,7 @@ class EtsPlanCheckReport(C.Structure):
 
 class EtsProfile(C.Structure):
     _fields_ = [("calls", C.c_int64), ("stream_ms", C.c_double), ("cascade_ms", C.c_double),
-                ("merge_ms", C.c_double)]
+                ("merge_ms", C.c_double), ("wide_ms", C.c_double)]
 
 
 def library_path() -> str:

@@ -37,6 +37,7 @@ struct ets_ctx {
     Run* d_runs = nullptr;
     StreamItem* d_stream = nullptr;
     CascadeItem* d_cascade = nullptr;
+    CascadeItem* d_wide = nullptr;
     int32_t* d_ent_order = nullptr;
     int32_t* d_part_base = nullptr;
     int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
@@ -52,7 +53,7 @@ struct ets_ctx {
     hipStream_t last_stream = nullptr;
     bool stream_used = false;
     void* static_scratch = nullptr;  // this device's copy of `scratch` (null: host-only context)
-    // kernel timing (benchmarks only): four events per recorded call
+    // kernel timing (benchmarks only): five events per recorded call
     bool profile = false;
     std::vector<hipEvent_t> events;
     size_t calls_recorded = 0;
@@ -131,6 +132,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
     const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
+    const size_t b_wide = align_up(p.wide_items.size() * sizeof(CascadeItem), 256);
     // Both per-entry tables end in kEntryPadding zero entries (leaf query 0, slot 0): a
     // wave's 16-entry scalar load may run past the item's last entry (check_plan replays
     // how far).
@@ -141,7 +143,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
     const size_t b_arow = align_up(p.adv_last_row.size() * sizeof(int64_t), 256);
     const size_t total =
-        b_runs + b_stream + b_casc + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
+        b_runs + b_stream + b_casc + b_wide + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -156,6 +158,8 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
         put(p.stream_items.data(), p.stream_items.size() * sizeof(StreamItem), b_stream);
     const size_t o_casc =
         put(p.cascade_items.data(), p.cascade_items.size() * sizeof(CascadeItem), b_casc);
+    const size_t o_wide =
+        put(p.wide_items.data(), p.wide_items.size() * sizeof(CascadeItem), b_wide);
     const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
     const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
     const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
@@ -184,6 +188,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     c->d_runs = reinterpret_cast<Run*>(c->d_buf + o_runs);
     c->d_stream = reinterpret_cast<StreamItem*>(c->d_buf + o_stream);
     c->d_cascade = reinterpret_cast<CascadeItem*>(c->d_buf + o_casc);
+    c->d_wide = reinterpret_cast<CascadeItem*>(c->d_buf + o_wide);
     c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
     c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
     c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
@@ -225,6 +230,32 @@ void launch_stream_g(const ets_ctx* c, const LaunchArgs& a) {
     }
 }
 
+// Segments shared by many leaf queries: the step-prefill kernel in its decode mode, 256 query
+// rows per workgroup, partial results into the same workspace slots.
+void launch_wide_attn(const ets_ctx* c, const LaunchArgs& a) {
+    const int64_t n_items = (int64_t)c->plan.wide_items.size();
+    if (n_items <= 0) return;
+    const int g = c->shape.n_q_heads / c->shape.n_kv_heads;
+    const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
+    for (int64_t y0 = 0; y0 < n_items; y0 += 65535) {
+        const unsigned ny = (unsigned)std::min<int64_t>(65535, n_items - y0);
+        if (c->kv_format == ETS_KV_FP8_E4M3)
+            hipLaunchKernelGGL((prefill_attn_kernel<true, true>),
+                               dim3((unsigned)c->shape.n_kv_heads, ny), dim3(512), 0, a.stream, a.k,
+                               a.v, a.pool_tokens, static_cast<const bf16_t*>(a.q), c->d_runs,
+                               c->d_wide, (int)y0, g_shift, c->scale * 1.4426950408889634f,
+                               c->k_scales, c->v_scales, a.ws_o, nullptr, c->d_ent_order,
+                               c->d_ent_base, a.ws_ml);
+        else
+            hipLaunchKernelGGL((prefill_attn_kernel<false, true>),
+                               dim3((unsigned)c->shape.n_kv_heads, ny), dim3(512), 0, a.stream, a.k,
+                               a.v, a.pool_tokens, static_cast<const bf16_t*>(a.q), c->d_runs,
+                               c->d_wide, (int)y0, g_shift, c->scale * 1.4426950408889634f,
+                               c->k_scales, c->v_scales, a.ws_o, nullptr, c->d_ent_order,
+                               c->d_ent_base, a.ws_ml);
+    }
+}
+
 void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     const int64_t n_items = (int64_t)c->plan.cascade_items.size();
     if (n_items <= 0) return;
@@ -240,13 +271,13 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
             hipLaunchKernelGGL(tree_attn_kernel<true>, dim3((unsigned)c->shape.n_kv_heads, ny),
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
                                static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
-                               (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
+                               (int)n_single, (int)n_items, (int)c->plan.wave_period, c->d_ent_order, c->d_ent_base, g_shift,
                                c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
         else
             hipLaunchKernelGGL(tree_attn_kernel<false>, dim3((unsigned)c->shape.n_kv_heads, ny),
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
                                static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
-                               (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
+                               (int)n_single, (int)n_items, (int)c->plan.wave_period, c->d_ent_order, c->d_ent_base, g_shift,
                                c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
     }
 }
@@ -297,10 +328,10 @@ ets_status upload_prefill_plan_unguarded(ets_ctx* c) {
 
 constexpr size_t kMaxProfiledCalls = 8192;
 
-// Event `which` (0..3) of the call being recorded, created on first use.
+// Event `which` (0..4) of the call being recorded, created on first use.
 void mark(ets_ctx* c, int which, hipStream_t stream) {
     if (!c->profile || c->calls_recorded >= kMaxProfiledCalls) return;
-    const size_t idx = c->calls_recorded * 4 + (size_t)which;
+    const size_t idx = c->calls_recorded * 5 + (size_t)which;
     while (c->events.size() <= idx) {
         hipEvent_t e = nullptr;
         if (hipEventCreate(&e) != hipSuccess) {
@@ -333,8 +364,10 @@ void launch_all(ets_ctx* c, const LaunchArgs& a, bool timed) {
         else launch_stream_g<float, 64>(c, a);
     }
     mark(c, 1, a.stream);
-    launch_tree_attn(c, a);
+    launch_wide_attn(c, a);
     mark(c, 2, a.stream);
+    launch_tree_attn(c, a);
+    mark(c, 3, a.stream);
     const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
     const unsigned grid = (unsigned)((pairs + 3) / 4);
     const HeadScales& out_scale = c->v_scales;
@@ -356,7 +389,7 @@ void launch_all(ets_ctx* c, const LaunchArgs& a, bool timed) {
         hipLaunchKernelGGL((merge_kernel<64, float>), dim3(grid), dim3(256), 0, a.stream,
                            c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
                            static_cast<float*>(a.out), a.lse, out_scale, group);
-    mark(c, 3, a.stream);
+    mark(c, 4, a.stream);
     if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
     if (!timed) c->profile = was_profiling;
 }
@@ -458,7 +491,12 @@ void ets_destroy(ets_ctx* ctx) {
 }
 
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
-    if (!ctx || !key || value < 0) return ETS_ERR_INVALID_ARG;
+    if (!ctx || !key) return ETS_ERR_INVALID_ARG;
+    if (!std::strcmp(key, "wide_rows") && value == -1) {
+        ctx->opt.wide_rows = -1;
+        return ETS_OK;
+    }
+    if (value < 0) return ETS_ERR_INVALID_ARG;
     if (!std::strcmp(key, "stream_chunk")) ctx->opt.stream_chunk = value;
     else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
     else if (!std::strcmp(key, "cascade_min_leaves")) ctx->opt.cascade_min_leaves = value;
@@ -466,6 +504,8 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
         if (value != 16 && value != 32 && value != 64) return ETS_ERR_INVALID_ARG;
         ctx->opt.cascade_rows = value;
     } else if (!std::strcmp(key, "wave_items")) ctx->opt.wave_items = value;
+    else if (!std::strcmp(key, "interleave")) ctx->opt.interleave = value != 0;
+    else if (!std::strcmp(key, "wide_rows")) ctx->opt.wide_rows = value;
     else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
     else if (!std::strcmp(key, "require_sharing")) ctx->opt.require_sharing = value != 0;
     else if (!std::strcmp(key, "out_bf16")) ctx->out_bf16 = value != 0;
@@ -786,17 +826,17 @@ ets_status ets_tree_prefill_attn(ets_ctx* ctx, const void* k_pool, const void* v
     for (int64_t y0 = 0; y0 < st.n_items; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, st.n_items - y0);
         if (ctx->kv_format == ETS_KV_FP8_E4M3)
-            hipLaunchKernelGGL(prefill_attn_kernel<true>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
+            hipLaunchKernelGGL((prefill_attn_kernel<true, false>), dim3((unsigned)ctx->shape.n_kv_heads, ny),
                                dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
                                static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
                                (int)y0, g_shift, ctx->scale * 1.4426950408889634f, ctx->k_scales,
-                               ctx->v_scales, out, lse);
+                               ctx->v_scales, out, lse, nullptr, nullptr, nullptr);
         else
-            hipLaunchKernelGGL(prefill_attn_kernel<false>, dim3((unsigned)ctx->shape.n_kv_heads, ny),
+            hipLaunchKernelGGL((prefill_attn_kernel<false, false>), dim3((unsigned)ctx->shape.n_kv_heads, ny),
                                dim3(512), 0, stream, k_pool, v_pool, pool_tokens,
                                static_cast<const bf16_t*>(q), ctx->d_pre_runs, ctx->d_pre_items,
                                (int)y0, g_shift, ctx->scale * 1.4426950408889634f, ctx->k_scales,
-                               ctx->v_scales, out, lse);
+                               ctx->v_scales, out, lse, nullptr, nullptr, nullptr);
     }
     ctx->last_stream = stream;
     ctx->stream_used = true;
@@ -871,18 +911,19 @@ ets_status ets_profile_read(ets_ctx* ctx, ets_profile* out) {
     if (!guard.ok) return ETS_ERR_HIP;
     const size_t n = ctx->calls_recorded;
     ctx->calls_recorded = 0;
-    if (hipEventSynchronize(ctx->events[n * 4 - 1]) != hipSuccess) return ETS_ERR_HIP;
+    if (hipEventSynchronize(ctx->events[n * 5 - 1]) != hipSuccess) return ETS_ERR_HIP;
     for (size_t i = 0; i < n; ++i) {
-        float ms[3] = {0.f, 0.f, 0.f};
-        for (int k = 0; k < 3; ++k)
-            if (hipEventElapsedTime(&ms[k], ctx->events[i * 4 + k], ctx->events[i * 4 + k + 1]) !=
+        float ms[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < 4; ++k)
+            if (hipEventElapsedTime(&ms[k], ctx->events[i * 5 + k], ctx->events[i * 5 + k + 1]) !=
                 hipSuccess) {
                 (void)hipGetLastError();
                 return ETS_ERR_HIP;
             }
         out->stream_ms += ms[0];
-        out->cascade_ms += ms[1];
-        out->merge_ms += ms[2];
+        out->wide_ms += ms[1];
+        out->cascade_ms += ms[2];
+        out->merge_ms += ms[3];
     }
     out->calls = (int64_t)n;
     return ETS_OK;

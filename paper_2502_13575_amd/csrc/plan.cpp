@@ -25,6 +25,7 @@ struct Seg {
     int32_t prefix = 0;          // partial slots used by the segments above
     int32_t n_chunks = 0;
     bool cascade = false;
+    bool wide = false;           // read by the wide kernel (many query rows)
 };
 
 struct Chunk {
@@ -192,6 +193,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     p.runs.clear();
     p.stream_items.clear();
     p.cascade_items.clear();
+    p.wide_items.clear();
     p.ent_order.assign(L, 0);
     p.part_base.assign((size_t)L + 1, 0);
     p.max_cascade_ent = 0;
@@ -246,12 +248,27 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // t_tile per tile whether it waits on memory (few rows) or computes (many rows)
     const int64_t t_tile = 1500, t_mem = t_tile, kTile = 64;
     auto tile_cost = [&](int64_t) { return t_tile; };
-    int64_t own_total = 0, work_ns = 0;
+    // wide kernel: one workgroup per compute unit, about t_wide per 64-token tile of 256 rows
+    // measured: on the 8-heads-per-kv-head shapes the wide kernel gains 5 % on a batch of
+    // searches; with 4 heads per kv head items of 64 rows are as fast
+    const int64_t wide_rows = opt.wide_rows >= 0 ? opt.wide_rows : (G >= 8 ? 64 : 0);
+    const int64_t ent_per_wide = std::max<int64_t>(1, kWideRowsPerItem / G);
+    const int64_t t_wide = 1500;
+    int64_t own_total = 0, work_ns = 0, wide_work_ns = 0;
     for (Seg& sg : segs) {
         sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
                      sg.tokens > 0 &&
                      (sg.cnt - 1) * sg.tokens * tok_bytes > sg.cnt * partial_bytes;
-        if (sg.cascade) {
+        // A segment with many query rows is work for the matrix cores, not for the memory
+        // system: items of 64 rows would stream it rows / 64 times through the compute
+        // units.  The wide kernel takes 256 rows per item.
+        sg.wide = sg.cascade && wide_rows > 0 && sg.cnt * G > wide_rows;
+        if (sg.wide) {
+            st.cascade_tokens += sg.tokens;
+            st.wide_tokens += sg.tokens;
+            wide_work_ns += ceil_div(sg.tokens, kTile) * ceil_div(sg.cnt, ent_per_wide) * t_wide *
+                            shape.n_kv_heads;
+        } else if (sg.cascade) {
             st.cascade_tokens += sg.tokens;
             for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item)
                 work_ns += ceil_div(sg.tokens, kTile) *
@@ -269,6 +286,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // of loads, not by their bytes, and finer items would only add partial results)
     const int64_t hbm_ns = st.unique_kv_bytes * (esz < 2 ? 2 : 1) / 5500;
     const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 1024) / 3, 4 * t_mem);
+
+    // wide items: no longer than a quarter of the time their launch is expected to take on
+    // 256 compute units, and not so short that start-up dominates
+    const int64_t wide_budget_ns = std::max<int64_t>(wide_work_ns / 256 / 4, 16 * t_wide);
 
     int64_t scap = opt.stream_chunk;
     if (scap <= 0) {
@@ -289,7 +310,9 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         sg.n_chunks = 0;
         if (!sg.cascade) continue;
         int64_t ccap = opt.cascade_chunk;
-        if (ccap <= 0)
+        if (ccap <= 0 && sg.wide)
+            ccap = wide_budget_ns / t_wide * kTile;
+        else if (ccap <= 0)
             ccap = item_budget_ns / tile_cost(std::min(ent_per_item, sg.cnt) * G) * kTile;
         tmp_runs.clear();
         if (!collect_runs(p, sg.nodes, own, tmp_runs)) p.adv_in_place = false;
@@ -343,10 +366,21 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         p.part_base[L] = (int32_t)slot;
     }
 
+    std::vector<int64_t> wide_cost;
     for (size_t s = 0; s < segs.size(); ++s) {
         const Seg& sg = segs[s];
         for (int32_t c = 0; c < sg.n_chunks; ++c) {
             const Chunk& ch = seg_chunks[s][c];
+            if (sg.wide) {
+                for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_wide) {
+                    const int32_t ne = (int32_t)std::min<int64_t>(ent_per_wide, sg.cnt - e0);
+                    p.wide_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
+                                                       sg.ent_begin + (int32_t)e0, ne, sg.prefix + c,
+                                                       ch.tokens, sg.cnt <= ent_per_wide ? 1 : 0, 0});
+                    wide_cost.push_back(ceil_div(ch.tokens, kTile) * ceil_div((int64_t)ne * G, 32));
+                }
+                continue;
+            }
             for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item) {
                 const int32_t ne = (int32_t)std::min<int64_t>(ent_per_item, sg.cnt - e0);
                 p.cascade_items.push_back(CascadeItem{ch.run_begin, ch.run_end,
@@ -371,6 +405,15 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         p.stream_items.swap(sorted);
     }
     {
+        std::vector<int32_t> idx(p.wide_items.size());
+        for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
+        std::stable_sort(idx.begin(), idx.end(),
+                         [&](int32_t a, int32_t b) { return wide_cost[a] > wide_cost[b]; });
+        std::vector<CascadeItem> sorted(idx.size());
+        for (size_t i = 0; i < idx.size(); ++i) sorted[i] = p.wide_items[idx[i]];
+        p.wide_items.swap(sorted);
+    }
+    {
         std::vector<int32_t> idx(p.cascade_items.size());
         for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int32_t)i;
         std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
@@ -393,6 +436,12 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         for (size_t i = 0; i < idx.size(); ++i)
             if (small(p.cascade_items[idx[i]])) sorted.push_back(p.cascade_items[idx[i]]);
         p.cascade_items.swap(sorted);
+        // The small items stream their rows at the memory system's pace and use the matrix
+        // cores little; the others are the opposite.  Spread evenly through the launch
+        // order, both kinds share every compute unit at all times.
+        const int64_t n_w = ((int64_t)p.cascade_items.size() - p.n_single + 3) / 4;
+        const int64_t total = p.n_single + n_w;
+        p.wave_period = opt.interleave && n_w > 0 && total / n_w >= 2 ? (int32_t)(total / n_w) : 0;
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
@@ -421,6 +470,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         return ETS_ERR_UNSUPPORTED;
     st.n_stream_items = (int64_t)p.stream_items.size();
     st.n_cascade_items = (int64_t)p.cascade_items.size();
+    st.n_wide_items = (int64_t)p.wide_items.size();
     st.workspace_bytes = st.n_partials * shape.n_q_heads * ((int64_t)shape.head_dim + 2) * 4;
     p.valid = true;
     return ETS_OK;
@@ -542,6 +592,29 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
                 std::max(out.max_partial_row, slot * shape.n_q_heads + shape.n_q_heads - 1);
         }
     }
+    // wide items: a lane looks up the entry of its own query row, clamped to the item's last
+    for (const CascadeItem& it : p.wide_items) {
+        out.items += 1;
+        bad(it.run_begin < 0 || it.run_end < it.run_begin || it.run_end > n_runs);
+        bad(it.n_ent < 1 || (int64_t)it.n_ent * G > kWideRowsPerItem || it.ent_begin < 0 ||
+            (int64_t)it.ent_begin + it.n_ent > L);
+        out.max_entry_index = std::max(out.max_entry_index, (int64_t)it.ent_begin + it.n_ent - 1);
+        for (int64_t r = it.run_begin; r < it.run_end && r < n_runs; ++r) {
+            const Run& run = p.runs[(size_t)r];
+            bad(run.n < 0 || run.n > 32 || run.tok < 0);
+            if (run.n > 0) {
+                bad(run.tok + run.n > p.stats.min_pool_tokens);
+                out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+        for (int32_t e = 0; e < it.n_ent && (int64_t)it.ent_begin + e < L; ++e) {
+            const int32_t leaf = p.ent_order[(size_t)(it.ent_begin + e)];
+            const int64_t slot = (int64_t)p.part_base[(size_t)leaf] + it.slot_off;
+            bad(it.slot_off < 0 || slot >= p.part_base[(size_t)leaf + 1]);
+            out.max_partial_row =
+                std::max(out.max_partial_row, slot * shape.n_q_heads + shape.n_q_heads - 1);
+        }
+    }
     for (const StreamItem& it : p.stream_items) {
         out.items += 1;
         bad(it.run_begin < 0 || it.run_end < it.run_begin || it.run_end > n_runs);
@@ -580,10 +653,11 @@ bool leaf_cover(const Plan& plan, int32_t leaf, std::vector<int64_t>& rows,
     };
     for (const StreamItem& it : plan.stream_items)
         if (it.entry == leaf) put(it.slot, it.run_begin, it.run_end);
-    for (const CascadeItem& it : plan.cascade_items)
-        for (int32_t i = 0; i < it.n_ent; ++i)
-            if (plan.ent_order[it.ent_begin + i] == leaf)
-                put(base + it.slot_off, it.run_begin, it.run_end);
+    for (const std::vector<CascadeItem>* items : {&plan.cascade_items, &plan.wide_items})
+        for (const CascadeItem& it : *items)
+            for (int32_t i = 0; i < it.n_ent; ++i)
+                if (plan.ent_order[it.ent_begin + i] == leaf)
+                    put(base + it.slot_off, it.run_begin, it.run_end);
     rows.clear();
     for (const auto& rr : by_slot) {
         if (rr.first < 0) {

@@ -58,6 +58,7 @@ struct AdvEntry {
 // Geometry of the matrix-core kernel that the planner and the launch code rely on.
 constexpr int kTreeAttnRowsPerItem = 64;  // query rows one work item serves at most
 constexpr int kTreeAttnMaxSteps = 256;    // steps per work item that takes a workgroup
+constexpr int kWideRowsPerItem = 256;     // query rows per work item of the wide kernel (8 waves x 32)
 // Both per-entry tables (ent_order, ent_base) end in this many zero entries on the device:
 // a wave fetches the entries of its 16 query rows with one 16-entry scalar load, which may
 // run up to 15 entries past the item's last entry (see check_plan).
@@ -75,6 +76,10 @@ struct PlanOptions {
                                      // walked by one wave, four such items to a workgroup (0 = off)
     int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
+    int64_t wide_rows = -1;          // a shared segment with more query rows than this goes to the
+                                     // wide kernel, 256 rows per item (0 = never; -1 = by the
+                                     // head geometry: 64 with 8 query heads per kv head, else never)
+    int64_t interleave = 1;          // 1 = workgroups of small items are spread among the others
     int64_t require_sharing = 0;     // 1 = a tree-mode plan that cannot share nodes is refused
 };
 
@@ -89,12 +94,16 @@ struct Plan {
     std::vector<Run> runs;
     std::vector<StreamItem> stream_items;
     std::vector<CascadeItem> cascade_items;
+    std::vector<CascadeItem> wide_items;  // up to kWideRowsPerItem query rows each, any number of runs
     std::vector<int32_t> ent_order;   // leaf queries in depth-first segment order
     std::vector<int32_t> part_base;   // [L + 1] first partial slot of every leaf query
     std::vector<int32_t> ent_base;    // [L] part_base of ent_order[i], for the kernel's scalar loads
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
     int32_t n_single = 0;             // cascade_items[0, n_single): one workgroup each; the rest:
                                       // small items, four to a workgroup (one wave each)
+    int32_t wave_period = 0;          // k >= 2: every k-th workgroup of the launch (k - 1, 2 k - 1,
+                                      // ...) holds small items until those are used up; 0: the
+                                      // small-item workgroups follow all the others
     // decode-step advance: every distinct node of leaf_node grows by one token
     std::vector<AdvEntry> adv;        // tails to extend
     std::vector<int32_t> adv_node;    // distinct leaf nodes, in order of first appearance

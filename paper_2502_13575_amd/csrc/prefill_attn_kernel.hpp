@@ -45,6 +45,14 @@
 // waves 4..7 of V.  The run list can be long (a
 // path of thousands of rows), so its descriptors travel through a ring of 256 entries in
 // LDS that is refilled 128 at a time, 64 tiles ahead of their use.
+//
+// The same kernel serves decode attention for tree segments that MANY leaf queries share
+// (template parameter DECODE): there the 256 query rows of a work item are up to 256 / G
+// leaf queries x the G query heads of the kv head, every row sees every row of the item's
+// runs, and instead of a normalised output the workgroup leaves the unnormalised partial
+// (o, m, l) of each query row in the decode workspace, where the log-sum-exp merge picks
+// it up.  A root prompt shared by 512 leaves is 2048 query rows per kv head: that is this
+// kernel's shape of problem (bound by the matrix cores), not the streaming kernel's.
 #pragma once
 
 #include "device_utils.hpp"
@@ -169,12 +177,18 @@ __device__ __forceinline__ float prefill_unit(const u32x4_t* __restrict__ ks_nex
 // FP8: the pools hold E4M3 codes (128-byte rows, 8 bytes per lane and load); the codes are
 // widened while the tile is staged (K to bf16, V straight to the fp16 fragments), the kv
 // head's K scale enters the score scale and its V scale multiplies the normalised rows.
-template <bool FP8>
+// DECODE: `items_raw` are CascadeItem (leaf queries ent_order[ent_begin .. + n_ent), at most
+// 256 / G of them), `out` is the partial workspace ws_o, `lse` is unused, and ent_order,
+// ent_base, ws_ml are the decode plan's tables; otherwise `items_raw` are PrefillItem and
+// the last three arguments are unused.
+template <bool FP8, bool DECODE>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ runs,
-    const PrefillItem* __restrict__ items, int item_base, int g_shift, float scale_log2e_base,
-    HeadScales k_scales, HeadScales v_scales, float* __restrict__ out, float* __restrict__ lse) {
+    const void* __restrict__ items_raw, int item_base, int g_shift, float scale_log2e_base,
+    HeadScales k_scales, HeadScales v_scales, float* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base,
+    float2* __restrict__ ws_ml) {
     constexpr int D = 128;
     constexpr int KROW = kTreeAttnKRow;
     constexpr int KS_UNITS = 64 * KROW;    // K tile: 64 rows of 272 bytes
@@ -196,12 +210,30 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     const int g = lane >> 5;
     const int h = blockIdx.x;
     const float scale_log2e = FP8 ? scale_log2e_base * k_scales.s[h] : scale_log2e_base;
-    const PrefillItem it = items[item_base + (int)blockIdx.y];
+    // the work item, in the terms both modes share: its runs, and the number of row
+    // groups (query tokens, or leaf queries) whose G heads make up its query rows
+    int run_begin, run_end, n_grp, tok0 = 0, ent_begin = 0, slot_off = 0;
+    int64_t q_row0 = 0;
+    if constexpr (DECODE) {
+        const CascadeItem it = static_cast<const CascadeItem*>(items_raw)[item_base + (int)blockIdx.y];
+        run_begin = it.run_begin;
+        run_end = it.run_end;
+        n_grp = it.n_ent;
+        ent_begin = it.ent_begin;
+        slot_off = it.slot_off;
+    } else {
+        const PrefillItem it = static_cast<const PrefillItem*>(items_raw)[item_base + (int)blockIdx.y];
+        run_begin = it.run_begin;
+        run_end = it.run_end;
+        n_grp = it.n_tok;
+        tok0 = it.tok0;
+        q_row0 = it.q_row0;
+    }
     const int G = 1 << g_shift;
     const int n_q_heads = n_kv_heads << g_shift;
-    const int n_runs = it.run_end - it.run_begin;
+    const int n_runs = run_end - run_begin;
     const int n_tiles = (n_runs + 1) >> 1;
-    const Run* my_runs = runs + it.run_begin;
+    const Run* my_runs = runs + run_begin;
     const float raise_margin = 8.0f / scale_log2e;
 
     // the wave's 16 rows of K (rows b + 4 i) or of V (rows 4 b + i) of two tiles in flight:
@@ -310,15 +342,26 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
 
     // row r = 32 w + n of the item is token r >> g_shift of the block, query head
     // r & (G - 1) of the kv head's group; rows past the block repeat its last token
+    // (decode: row r is leaf query r >> g_shift of the item, in ent_order)
     const int r_lane = 32 * w + n;
-    const int tq_lane = min(r_lane >> g_shift, it.n_tok - 1);
-    const int i_row = it.tok0 + tq_lane;  // the lane's query token, as an index into its node
+    const int tq_lane = min(r_lane >> g_shift, n_grp - 1);
+    const int i_row = tok0 + tq_lane;  // the lane's query token, as an index into its node
     // a wave whose 32 rows all lie past the block's last token (the last block of a node
     // is rarely full) only fetches and stages: its SIMD is left to the other wave
-    const bool active = ((32 * w) >> g_shift) < it.n_tok;
+    const bool active = ((32 * w) >> g_shift) < n_grp;
     bf16x8_t qf[8];
+    int64_t out_row;  // row of the lane's query in `out` (and in lse / ws_ml)
     {
-        const bf16_t* qp = q + ((it.q_row0 + tq_lane) * n_q_heads + h * G + (r_lane & (G - 1))) * D;
+        const int head = h * G + (r_lane & (G - 1));
+        int64_t q_row;
+        if constexpr (DECODE) {
+            q_row = ent_order[ent_begin + tq_lane];
+            out_row = (int64_t)(ent_base[ent_begin + tq_lane] + slot_off) * n_q_heads + head;
+        } else {
+            q_row = q_row0 + tq_lane;
+            out_row = q_row * n_q_heads + head;
+        }
+        const bf16_t* qp = q + (q_row * n_q_heads + head) * D;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(load16(qp + 16 * kk + 8 * g));
     }
@@ -340,6 +383,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     auto lim_of = [&](const u32x4_t& d) {
         // rows of the run that the lane's query row sees
         const int n_valid = __builtin_amdgcn_readfirstlane(d[2]);
+        if constexpr (DECODE) return n_valid;  // the query is newer than every row
         const int kpos = __builtin_amdgcn_readfirstlane(d[3]);
         return min(n_valid, i_row - kpos + 1);
     };
@@ -406,17 +450,24 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
     if (n_tiles & 1) do_tile(n_tiles - 1, raw0);
     __syncthreads();  // every wave is done with the tiles: the epilogue reuses the buffers
 
-    // normalised rows out through the wave's own LDS region (16 rows padded to 132 floats,
-    // two passes), so that whole 512-byte rows are stored
+    // rows out through the wave's own LDS region (16 rows padded to 132 floats, two
+    // passes), so that whole 512-byte rows are stored: normalised in step prefill,
+    // unnormalised next to (m, l) in decode
     constexpr int OROW = 132;
     float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
     float l = lsum;
     l += __shfl_xor(l, 32, 64);
-    float inv = 1.0f / l;
-    if constexpr (FP8) inv *= v_scales.s[h];
-    if (g == 0 && (r_lane >> g_shift) < it.n_tok)
-        lse[(it.q_row0 + tq_lane) * n_q_heads + h * G + (r_lane & (G - 1))] =
-            (m * scale_log2e + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    float inv = 1.0f;
+    if constexpr (!DECODE) {
+        inv = 1.0f / l;
+        if constexpr (FP8) inv *= v_scales.s[h];
+    }
+    if (g == 0 && (r_lane >> g_shift) < n_grp) {
+        if constexpr (DECODE)
+            ws_ml[out_row] = make_float2(m * scale_log2e, l);
+        else
+            lse[out_row] = (m * scale_log2e + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    }
     const int col = (lane & 31) * 4;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -435,11 +486,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void p
         for (int k = 0; k < 8; ++k) {
             const int rr = 2 * k + (lane >> 5);  // row of this pass that the lane stores
             const int r = 32 * w + 16 * pass + rr;
-            const int tq = r >> g_shift;
+            // lane 16 pass + rr (g = 0) holds the output row of query row r
+            const int64_t row_out = __shfl(out_row, 16 * pass + rr, 64);
             const float4 v = *reinterpret_cast<const float4*>(ob + rr * OROW + col);
-            if (tq < it.n_tok)
-                *reinterpret_cast<float4*>(
-                    out + ((it.q_row0 + tq) * n_q_heads + h * G + (r & (G - 1))) * D + col) = v;
+            if ((r >> g_shift) < n_grp) *reinterpret_cast<float4*>(out + row_out * D + col) = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();

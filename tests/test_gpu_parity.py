@@ -19,7 +19,11 @@ pytestmark = pytest.mark.gpu
 VARIANTS = {
     "tree": (ets.ETS_PLAN_TREE, {}),
     "tree_no_sharing": (ets.ETS_PLAN_TREE, {"cascade_min_leaves": 0}),
-    "tree_workgroup_items": (ets.ETS_PLAN_TREE, {"wave_items": 0}),
+    "tree_workgroup_items": (ets.ETS_PLAN_TREE, {"wave_items": 0, "interleave": 0}),
+    # every segment with more than 16 / 64 query rows through the wide kernel; none through it
+    "tree_wide16": (ets.ETS_PLAN_TREE, {"wide_rows": 16}),
+    "tree_wide64": (ets.ETS_PLAN_TREE, {"wide_rows": 64}),
+    "tree_no_wide": (ets.ETS_PLAN_TREE, {"wide_rows": 0}),
     "tree_valu_only": (ets.ETS_PLAN_TREE, {"mfma": 0}),
     "flat": (ets.ETS_PLAN_FLAT, {}),
 }
@@ -52,6 +56,11 @@ def test_configs_full_parity(name, variant):
     if variant == "tree" and cfg.dtype == "bf16":
         assert st.n_cascade_items > 0 and st.cascade_tokens > 0     # shared nodes on the MFMA path
         assert st.n_stream_items == 0
+    if (variant == "tree_wide16" or (variant == "tree_wide64" and name != "c2_w16")) \
+            and cfg.dtype == "bf16":
+        assert st.n_wide_items > 0 and 0 < st.wide_tokens <= st.cascade_tokens
+    if variant == "tree_no_wide":
+        assert st.n_wide_items == 0
     if variant == "tree_valu_only" or cfg.dtype == "f32":
         assert st.n_cascade_items == 0
     if variant in ("flat", "tree_no_sharing"):
@@ -129,7 +138,8 @@ def test_fuzz_irregular_forests(seed):
     tree = random_tree(seed, n_nodes=50, n_leaves=21, max_tokens=90)
     options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3],
                "cascade_rows": [64, 16, 32][(seed // 2) % 3],
-               "wave_items": [512, 0, 48, 100000][seed % 4]}
+               "wave_items": [512, 0, 48, 100000][seed % 4],
+               "wide_rows": [128, 16, 8, 40][(seed // 2) % 4]}
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):

@@ -259,7 +259,9 @@ def test_wide_random_sweep():
                    "cascade_chunk": int(r.choice([0, 32, 96])),
                    "cascade_rows": int(r.choice([64, 16, 32])),
                    "wave_items": int(r.choice([512, 0, 48, 100000])),
-                   "cascade_min_leaves": int(r.choice([2, 2, 0, 3]))}
+                   "cascade_min_leaves": int(r.choice([2, 2, 0, 3])),
+                   "wide_rows": int(r.choice([128, 16, 4, 40, 0])),
+                   "interleave": int(r.choice([1, 1, 0]))}
         mode = int(r.choice([ets.ETS_PLAN_TREE, ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT]))
         print("case sweep", seed, (hkv, hq), tree.n_nodes, tree.n_leaves, options, mode, flush=True)
         k, v, q = make_values_host(cfg, tree)

@@ -278,7 +278,7 @@ def test_plan_check_replays_kernel_accesses_on_configs():
                 ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
             rep = ctx.check()
             assert rep.violations == 0, name
-            assert rep.decode_items == st.n_cascade_items + st.n_stream_items
+            assert rep.decode_items == st.n_cascade_items + st.n_stream_items + st.n_wide_items
             assert rep.max_pool_row == st.min_pool_tokens - 1
             assert rep.max_partial_row == st.n_partials * cfg.n_q_heads - 1
             assert rep.max_entry_overreach <= 15
@@ -305,7 +305,9 @@ def test_plan_check_sweep_of_random_forests():
                 "cascade_rows": int(r.choice([64, 16, 32])),
                 "wave_items": int(r.choice([512, 0, 48, 100000])),
                 "cascade_min_leaves": int(r.choice([2, 0, 3, 9])),
-                "mfma": int(r.choice([1, 1, 0]))}
+                "mfma": int(r.choice([1, 1, 0])),
+                "wide_rows": int(r.choice([128, 0, 16, 40, 300])),
+                "interleave": int(r.choice([1, 0]))}
         mode = int(r.choice([0, 0, 1]))
         if seed % 3 == 0:
             t = with_growth_room(t, 40)
