@@ -128,6 +128,13 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
     for (int kk = 0; kk < 4; ++kk)
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[16 * KROW + 4 * kk]), qf[kk],
                                                      s1, 0, 0, 0);
+    // The first four V^T fragments are requested from LDS before the softmax arithmetic, so
+    // that they arrive while it runs; the other four follow behind the first matrix
+    // instructions.  (Left to itself the compiler reads each fragment just ahead of its use.)
+    u32x4_t vf[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) vf[x] = vs_lane[x * 64];
+    __builtin_amdgcn_sched_barrier(0);
     // lane holds row a of the block, tokens 4 b + i (first half) and 16 + 4 b + i (second half)
     float s[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
     if (n_valid < 32) {
@@ -157,10 +164,16 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
         psum += p;
         pf[j] = (_Float16)p;
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int x = 0; x < 8; ++x)
-        oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vs_lane[x * 64]), pf, oacc[x], 0,
-                                                         0, 0);
+    for (int x = 0; x < 4; ++x) {
+        oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vf[x]), pf, oacc[x], 0, 0, 0);
+        vf[x] = vs_lane[(4 + x) * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+        oacc[4 + x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vf[x]), pf, oacc[4 + x], 0, 0, 0);
     lsum += psum;
 }
 
