@@ -38,6 +38,7 @@ struct ets_ctx {
     StreamItem* d_stream = nullptr;
     CascadeItem* d_cascade = nullptr;
     CascadeItem* d_wide = nullptr;
+    int32_t* d_wg_map = nullptr;     // launch order of the matrix-core kernel
     int32_t* d_ent_order = nullptr;
     int32_t* d_part_base = nullptr;
     int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
@@ -133,6 +134,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
     const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
     const size_t b_wide = align_up(p.wide_items.size() * sizeof(CascadeItem), 256);
+    const size_t b_map = align_up(p.wg_map.size() * sizeof(int32_t), 256);
     // Both per-entry tables end in kEntryPadding zero entries (leaf query 0, slot 0): a
     // wave's 16-entry scalar load may run past the item's last entry (check_plan replays
     // how far).
@@ -143,7 +145,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
     const size_t b_arow = align_up(p.adv_last_row.size() * sizeof(int64_t), 256);
     const size_t total =
-        b_runs + b_stream + b_casc + b_wide + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
+        b_runs + b_stream + b_casc + b_wide + b_map + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -160,6 +162,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
         put(p.cascade_items.data(), p.cascade_items.size() * sizeof(CascadeItem), b_casc);
     const size_t o_wide =
         put(p.wide_items.data(), p.wide_items.size() * sizeof(CascadeItem), b_wide);
+    const size_t o_map = put(p.wg_map.data(), p.wg_map.size() * sizeof(int32_t), b_map);
     const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
     const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
     const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
@@ -189,6 +192,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     c->d_stream = reinterpret_cast<StreamItem*>(c->d_buf + o_stream);
     c->d_cascade = reinterpret_cast<CascadeItem*>(c->d_buf + o_casc);
     c->d_wide = reinterpret_cast<CascadeItem*>(c->d_buf + o_wide);
+    c->d_wg_map = reinterpret_cast<int32_t*>(c->d_buf + o_map);
     c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
     c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
     c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
@@ -264,20 +268,20 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     // grid: x = kv head, y = workgroup (at most 65535 per launch): first the items that
     // take a workgroup each, then the small ones, four to a workgroup
     const int64_t n_single = c->plan.n_single;
-    const int64_t n_wgs = n_single + (n_items - n_single + 3) / 4;
+    const int64_t n_wgs = (int64_t)c->plan.wg_map.size();
     for (int64_t y0 = 0; y0 < n_wgs; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
         if (c->kv_format == ETS_KV_FP8_E4M3)
             hipLaunchKernelGGL(tree_attn_kernel<true>, dim3((unsigned)c->shape.n_kv_heads, ny),
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
-                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
-                               (int)n_single, (int)n_items, (int)c->plan.wave_period, c->d_ent_order, c->d_ent_base, g_shift,
+                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_wg_map,
+                               (int)y0, (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
                                c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
         else
             hipLaunchKernelGGL(tree_attn_kernel<false>, dim3((unsigned)c->shape.n_kv_heads, ny),
                                dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
-                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, (int)y0,
-                               (int)n_single, (int)n_items, (int)c->plan.wave_period, c->d_ent_order, c->d_ent_base, g_shift,
+                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_wg_map,
+                               (int)y0, (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
                                c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
     }
 }

@@ -436,12 +436,54 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         for (size_t i = 0; i < idx.size(); ++i)
             if (small(p.cascade_items[idx[i]])) sorted.push_back(p.cascade_items[idx[i]]);
         p.cascade_items.swap(sorted);
-        // The small items stream their rows at the memory system's pace and use the matrix
-        // cores little; the others are the opposite.  Spread evenly through the launch
-        // order, both kinds share every compute unit at all times.
+        // Launch order.  Items with many query rows keep a workgroup slot busy for a long
+        // time per byte they bring in from memory; items with few rows (a leaf's private
+        // rows, segments shared by a handful of leaves) stream at the memory system's pace.
+        // The device hands workgroups out in index order, so the two kinds are merged into
+        // one sequence in which each advances at the same fraction of its total tokens:
+        // memory traffic and arithmetic are then spread evenly over the launch instead of
+        // following each other.  Within a kind the order stays longest first.
         const int64_t n_w = ((int64_t)p.cascade_items.size() - p.n_single + 3) / 4;
-        const int64_t total = p.n_single + n_w;
-        p.wave_period = opt.interleave && n_w > 0 && total / n_w >= 2 ? (int32_t)(total / n_w) : 0;
+        std::vector<std::pair<int64_t, int32_t>> heavy, light;  // (tokens, code)
+        for (int32_t i = 0; i < p.n_single; ++i) {
+            const CascadeItem& it = p.cascade_items[(size_t)i];
+            ((int64_t)it.n_ent * G > 16 ? heavy : light).push_back({it.n_tokens, i});
+        }
+        for (int64_t g = 0; g < n_w; ++g) {
+            int64_t tok = 0;
+            for (int64_t k = 4 * g; k < std::min<int64_t>(4 * g + 4, (int64_t)p.cascade_items.size() - p.n_single); ++k)
+                tok += p.cascade_items[(size_t)(p.n_single + k)].n_tokens;
+            light.push_back({tok, (int32_t)(-g - 1)});
+        }
+        p.wg_map.clear();
+        p.wg_map.reserve(heavy.size() + light.size());
+        if (!opt.interleave) {
+            for (int32_t i = 0; i < p.n_single; ++i) p.wg_map.push_back(i);
+            for (int64_t g = 0; g < n_w; ++g) p.wg_map.push_back((int32_t)(-g - 1));
+        } else {
+            auto by_tokens = [](const std::pair<int64_t, int32_t>& a,
+                                const std::pair<int64_t, int32_t>& b) { return a.first > b.first; };
+            std::stable_sort(heavy.begin(), heavy.end(), by_tokens);
+            std::stable_sort(light.begin(), light.end(), by_tokens);
+            int64_t tot_h = 0, tot_l = 0, done_h = 0, done_l = 0;
+            for (const auto& x : heavy) tot_h += std::max<int64_t>(x.first, 1);
+            for (const auto& x : light) tot_l += std::max<int64_t>(x.first, 1);
+            size_t ih = 0, il = 0;
+            while (ih < heavy.size() || il < light.size()) {
+                // the kind that lags behind in its own total goes next (fractions compared
+                // without division: done_h / tot_h <= done_l / tot_l)
+                const bool take_heavy =
+                    il >= light.size() ||
+                    (ih < heavy.size() && (__int128)done_h * tot_l <= (__int128)done_l * tot_h);
+                if (take_heavy) {
+                    p.wg_map.push_back(heavy[ih].second);
+                    done_h += std::max<int64_t>(heavy[ih++].first, 1);
+                } else {
+                    p.wg_map.push_back(light[il].second);
+                    done_l += std::max<int64_t>(light[il++].first, 1);
+                }
+            }
+        }
     }
 
     if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
@@ -629,6 +671,21 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
             if (run.n > 0) {
                 bad(run.tok + run.n > p.stats.min_pool_tokens);
                 out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+    }
+    // the launch order names every item that takes a workgroup and every group of small
+    // items exactly once
+    {
+        const int64_t n_w = ((int64_t)p.cascade_items.size() - p.n_single + 3) / 4;
+        bad((int64_t)p.wg_map.size() != p.n_single + n_w);
+        std::vector<char> seen_single((size_t)p.n_single, 0), seen_group((size_t)n_w, 0);
+        for (int32_t code : p.wg_map) {
+            if (code >= 0) {
+                if (code >= p.n_single || seen_single[(size_t)code]++) out.violations += 1;
+            } else {
+                const int64_t g = -(int64_t)code - 1;
+                if (g >= n_w || seen_group[(size_t)g]++) out.violations += 1;
             }
         }
     }

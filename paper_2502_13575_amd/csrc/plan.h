@@ -101,9 +101,9 @@ struct Plan {
     int32_t max_cascade_ent = 0;      // largest n_ent over the cascade items
     int32_t n_single = 0;             // cascade_items[0, n_single): one workgroup each; the rest:
                                       // small items, four to a workgroup (one wave each)
-    int32_t wave_period = 0;          // k >= 2: every k-th workgroup of the launch (k - 1, 2 k - 1,
-                                      // ...) holds small items until those are used up; 0: the
-                                      // small-item workgroups follow all the others
+    std::vector<int32_t> wg_map;      // launch order of the matrix-core kernel: workgroup i takes
+                                      // item wg_map[i] when that is >= 0, else the four small
+                                      // items of group -wg_map[i] - 1 (n_single + 4 g ..)
     // decode-step advance: every distinct node of leaf_node grows by one token
     std::vector<AdvEntry> adv;        // tails to extend
     std::vector<int32_t> adv_node;    // distinct leaf nodes, in order of first appearance

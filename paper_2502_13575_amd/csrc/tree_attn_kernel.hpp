@@ -231,7 +231,8 @@ template <bool FP8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
-    const CascadeItem* __restrict__ items, int wg_base, int n_single, int n_items, int wave_period,
+    const CascadeItem* __restrict__ items, const int32_t* __restrict__ wg_map, int wg_base,
+    int n_single, int n_items,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
     float scale_log2e_base, HeadScales k_scales,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
@@ -258,23 +259,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int h = blockIdx.x;  // kv head; consecutive workgroups share an item
     // E4M3 pools: the K scale of this kv head is part of the score scale
     const float scale_log2e = FP8 ? scale_log2e_base * k_scales.s[h] : scale_log2e_base;
-    // n_single workgroups take one item each; the others hold four small items, one per
-    // wave, which then works alone: no barrier below this point on that path.  The
-    // small-item workgroups either follow the others or, with wave_period k >= 2, are the
-    // workgroups k - 1, 2 k - 1, ... of the launch while they last.
-    const int wg = wg_base + (int)blockIdx.y;
-    bool wave_item;
-    int item_idx;
-    if (wave_period >= 2) {
-        const int n_wave_wgs = (n_items - n_single + 3) >> 2;
-        const int j = wg / wave_period;
-        wave_item = j < n_wave_wgs && wg - j * wave_period == wave_period - 1;
-        item_idx = wave_item ? n_single + 4 * j + w : wg - min(j, n_wave_wgs);
-        if (!wave_item && item_idx >= n_single) return;
-    } else {
-        wave_item = wg >= n_single;
-        item_idx = wave_item ? n_single + 4 * (wg - n_single) + w : wg;
-    }
+    // A workgroup takes one item, or four small items, one per wave, which then works alone
+    // (no barrier below this point on that path); the planner's launch order says which.
+    const int code = wg_map[wg_base + (int)blockIdx.y];  // uniform: a scalar load
+    const bool wave_item = code < 0;
+    const int item_idx = wave_item ? n_single + 4 * (-code - 1) + w : code;
     if (item_idx >= n_items) return;
     const CascadeItem it = items[item_idx];
     const int G = 1 << g_shift;
