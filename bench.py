@@ -139,11 +139,16 @@ def measure_config(ets, torch, name, dev, stream, steps=30, flat_steps=3):
             torch.cuda.synchronize()
             pr = ctx.profile_read()
             ctx.set_option("profile", 0)
-            k_us = (pr.cascade_ms if st.n_cascade_items > 0 else pr.stream_ms) / max(pr.calls, 1) * 1e3
+            # attention kernels of the call: the matrix-core kernel plus, when the plan has
+            # such items, the wide kernel that precedes it (or the streaming kernel)
+            k_us = ((pr.cascade_ms + (pr.wide_ms if st.n_wide_items > 0 else 0.0))
+                    if st.n_cascade_items > 0 else pr.stream_ms) / max(pr.calls, 1) * 1e3
             res.update({
                 "live_nodes": int(st.live_nodes), "unique_tokens": int(st.unique_tokens),
                 "unique_kv_bytes": int(st.unique_kv_bytes), "n_partials": int(st.n_partials),
-                "work_items": int(st.n_cascade_items + st.n_stream_items),
+                "work_items": int(st.n_cascade_items + st.n_stream_items + st.n_wide_items),
+                "wide_items": int(st.n_wide_items),
+                "wide_kernel_us": round(pr.wide_ms / max(pr.calls, 1) * 1e3, 2) if st.n_wide_items > 0 else 0.0,
                 "us_per_layer": round(us, 1),
                 "leaf_queries_per_s": round(L / (us * 1e-6), 1),
                 "unique_kv_GBps": round(st.unique_kv_bytes / (us * 1e-6) / 1e9, 1),
@@ -298,8 +303,9 @@ def main():
     # roofline of the dominant kernel: the algorithmic KV bytes of the items it reads
     # (unique tokens x 2 x Hkv x D x element size, each read once per launch)
     mfma_path = st.n_cascade_items > 0
+    # (segments that the wide kernel reads are its bytes, not the matrix-core kernel's)
     kern = {
-        "cascade": (prof.cascade_ms, st.unique_tokens * tok_bytes if mfma_path else 0),
+        "cascade": (prof.cascade_ms, (st.unique_tokens - st.wide_tokens) * tok_bytes if mfma_path else 0),
         "stream": (prof.stream_ms, 0 if mfma_path else st.unique_tokens * tok_bytes),
     }
     dom = max(kern, key=lambda k: kern[k][0])
@@ -775,8 +781,8 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "first_call_ms": round(first_call_ms, 1),
         "plan": {k: stats[k] for k in ("n_segments", "n_partials", "n_stream_items",
-                                       "n_cascade_items", "workspace_bytes", "cascade_tokens",
-                                       "stream_tokens")},
+                                       "n_cascade_items", "n_wide_items", "workspace_bytes",
+                                       "cascade_tokens", "wide_tokens", "stream_tokens")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "flat_baseline": flat,
