@@ -122,6 +122,8 @@ typedef struct {
                              /* 128, tree mode); 0: every leaf reads its chain itself    */
     int64_t n_wide_items;    /* work items of the kernel for widely shared segments      */
     int64_t wide_tokens;     /* unique tokens of those segments (part of cascade_tokens) */
+    int64_t merge_fused;     /* 1: the shared-node kernel merges the partials itself (no  */
+                             /* merge launch); see the "fuse_merge" option                */
 } ets_stats;
 
 typedef enum {
@@ -239,9 +241,19 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *   "wide_rows"      a shared segment with more query rows than this is read by the
  *                    wide kernel (256 query rows per work item, bound by the matrix
  *                    cores) instead of by several items of "cascade_rows" rows each
- *                    (0 = never; -1, the default = by the head geometry: 64 with 8 query
- *                    heads per kv head, where it measures 5 % faster on a batch of
- *                    searches, never with fewer, where items of 64 rows are as fast)
+ *                    (0 or -1 = never, the default: items of 64 rows in the merged launch
+ *                    order measure 5-6 % faster on every configuration tried)
+ *   "fuse_merge"     1 = the shared-node kernel also merges: the wavefront that stores a
+ *                    leaf query's last partial result combines them, and no merge kernel
+ *                    is launched.  Only for plans whose partial results all come from
+ *                    that kernel (bf16 or E4M3 pools with head_dim 128, no wide items),
+ *                    in which every leaf query has a token, and whose workspace is below
+ *                    2 GiB; other plans keep the merge launch (ets_stats.merge_fused
+ *                    tells).  Same results bit for bit.  The arrival counters belong to
+ *                    the context: calls of one context must then not overlap on the
+ *                    device.  0 or -1 = separate merge launch, the default: it measures
+ *                    faster (the device-scope round trips at the end of the last item
+ *                    cost more than the launch they replace)
  *   "interleave"     1 (default) = the workgroups that hold small items are spread through
  *                    the launch order; 0 = they follow all the others
  *   "wave_items"     a work item of at most 16 query rows and at most this many
@@ -259,7 +271,7 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *                    projection's input in bf16; 0 (default) = fp32.  Effective from
  *                    the next decode call; lse stays fp32
  *   "profile"        1 = record kernel times (see ets_profile_read), 0 = off
- * Unknown key or negative value (other than wide_rows = -1): ETS_ERR_INVALID_ARG. */
+ * Unknown key or negative value (other than -1 for wide_rows, fuse_merge): ETS_ERR_INVALID_ARG. */
 ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
 
 /* Storage format of the K/V pools.  The search is bound by the bytes of KV state that

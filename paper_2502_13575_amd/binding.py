@@ -40,7 +40,7 @@ class EtsStats(C.Structure):
         "n_nodes", "live_nodes", "n_leaves", "unique_tokens", "flat_tokens", "unique_kv_bytes",
         "flat_kv_bytes", "n_segments", "n_partials", "n_stream_items", "n_cascade_items",
         "min_pool_tokens", "workspace_bytes", "cascade_tokens", "stream_tokens", "shares_nodes",
-        "n_wide_items", "wide_tokens")]
+        "n_wide_items", "wide_tokens", "merge_fused")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -45,6 +45,7 @@ struct ets_ctx {
     AdvEntry* d_adv = nullptr;       // decode-step advance: tails to extend
     int32_t* d_adv_src = nullptr;    // per growing node: leaf query that supplies its new token
     int64_t* d_adv_last_row = nullptr;  // per growing node: newest pool row at plan time
+    int32_t* d_arrived = nullptr;    // merge inside the attention launch: [leaf][kv head] counters
     // step prefill: its own plan and device tables
     PrefillPlan prefill;
     char* d_pre_buf = nullptr;
@@ -144,8 +145,12 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_adv = align_up(p.adv.size() * sizeof(AdvEntry), 256);
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
     const size_t b_arow = align_up(p.adv_last_row.size() * sizeof(int64_t), 256);
-    const size_t total =
-        b_runs + b_stream + b_casc + b_wide + b_map + 2 * b_ent + b_base + b_adv + b_asrc + b_arow + 256;
+    // arrival counters of the merge inside the attention launch: zero here, and put back
+    // to zero by the kernel itself at the end of every call
+    const size_t b_arrived =
+        p.fused ? align_up((size_t)p.stats.n_leaves * c->shape.n_kv_heads * sizeof(int32_t), 256) : 0;
+    const size_t total = b_runs + b_stream + b_casc + b_wide + b_map + 2 * b_ent + b_base + b_adv +
+                         b_asrc + b_arow + b_arrived + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -169,6 +174,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t o_adv = put(p.adv.data(), p.adv.size() * sizeof(AdvEntry), b_adv);
     const size_t o_asrc = put(p.adv_src.data(), p.adv_src.size() * sizeof(int32_t), b_asrc);
     const size_t o_arow = put(p.adv_last_row.data(), p.adv_last_row.size() * sizeof(int64_t), b_arow);
+    const size_t o_arrived = put(nullptr, 0, b_arrived);
 
     DeviceGuard guard(c->device);
     if (!guard.ok) return ETS_ERR_HIP;
@@ -199,6 +205,7 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     c->d_adv = reinterpret_cast<AdvEntry*>(c->d_buf + o_adv);
     c->d_adv_src = reinterpret_cast<int32_t*>(c->d_buf + o_asrc);
     c->d_adv_last_row = reinterpret_cast<int64_t*>(c->d_buf + o_arow);
+    c->d_arrived = reinterpret_cast<int32_t*>(c->d_buf + o_arrived);
     return ETS_OK;
 }
 
@@ -269,20 +276,26 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     // take a workgroup each, then the small ones, four to a workgroup
     const int64_t n_single = c->plan.n_single;
     const int64_t n_wgs = (int64_t)c->plan.wg_map.size();
+    MergeTail tail{};
+    if (c->plan.fused) {
+        tail.part_base = c->d_part_base;
+        tail.arrived = c->d_arrived;
+        tail.n_ws_rows = c->plan.stats.n_partials * c->shape.n_q_heads;
+        tail.out = a.out;
+        tail.lse = a.lse;
+        tail.out_bf16 = c->out_bf16 ? 1 : 0;
+        tail.v_scales = c->v_scales;
+    }
     for (int64_t y0 = 0; y0 < n_wgs; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
-        if (c->kv_format == ETS_KV_FP8_E4M3)
-            hipLaunchKernelGGL(tree_attn_kernel<true>, dim3((unsigned)c->shape.n_kv_heads, ny),
-                               dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
-                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_wg_map,
-                               (int)y0, (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
-                               c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
-        else
-            hipLaunchKernelGGL(tree_attn_kernel<false>, dim3((unsigned)c->shape.n_kv_heads, ny),
-                               dim3(256), 0, a.stream, a.k, a.v, a.pool_tokens,
-                               static_cast<const bf16_t*>(a.q), c->d_runs, c->d_cascade, c->d_wg_map,
-                               (int)y0, (int)n_single, (int)n_items, c->d_ent_order, c->d_ent_base, g_shift,
-                               c->scale * 1.4426950408889634f, c->k_scales, a.ws_o, a.ws_ml);
+        const bool fp8 = c->kv_format == ETS_KV_FP8_E4M3;
+        auto kernel = c->plan.fused ? (fp8 ? tree_attn_kernel<true, true> : tree_attn_kernel<false, true>)
+                                    : (fp8 ? tree_attn_kernel<true, false> : tree_attn_kernel<false, false>);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0, a.stream,
+                           a.k, a.v, a.pool_tokens, static_cast<const bf16_t*>(a.q), c->d_runs,
+                           c->d_cascade, c->d_wg_map, (int)y0, (int)n_single, (int)n_items,
+                           c->d_ent_order, c->d_ent_base, g_shift, c->scale * 1.4426950408889634f,
+                           c->k_scales, a.ws_o, a.ws_ml, tail);
     }
 }
 
@@ -354,6 +367,31 @@ void mark(ets_ctx* c, int which, hipStream_t stream) {
     (void)hipEventRecord(c->events[idx], stream);
 }
 
+template <int D, int G>
+void launch_merge_dg(ets_ctx* c, const LaunchArgs& a) {
+    const int n_leaves = (int)c->plan.stats.n_leaves;
+    const int64_t pairs = (int64_t)n_leaves * c->shape.n_kv_heads;  // one wave each
+    const unsigned grid = (unsigned)((pairs + 3) / 4);
+    hipLaunchKernelGGL((merge_kernel<D, G>), dim3(grid), dim3(256), 0, a.stream, c->d_part_base,
+                       n_leaves, c->shape.n_kv_heads, a.ws_o, a.ws_ml, a.out, c->out_bf16 ? 1 : 0,
+                       a.lse, c->v_scales);
+}
+
+template <int D>
+void launch_merge_d(ets_ctx* c, const LaunchArgs& a) {
+    switch (c->shape.n_q_heads / c->shape.n_kv_heads) {
+        case 1: launch_merge_dg<D, 1>(c, a); break;
+        case 2: launch_merge_dg<D, 2>(c, a); break;
+        case 4: launch_merge_dg<D, 4>(c, a); break;
+        default: launch_merge_dg<D, 8>(c, a); break;
+    }
+}
+
+void launch_merge(ets_ctx* c, const LaunchArgs& a) {
+    if (c->shape.head_dim == 128) launch_merge_d<128>(c, a);
+    else launch_merge_d<64>(c, a);
+}
+
 // `timed`: bracket the kernels with events when the "profile" option is on (may allocate)
 void launch_all(ets_ctx* c, const LaunchArgs& a, bool timed) {
     const bool bf = c->shape.dtype == ETS_BF16;
@@ -372,27 +410,7 @@ void launch_all(ets_ctx* c, const LaunchArgs& a, bool timed) {
     mark(c, 2, a.stream);
     launch_tree_attn(c, a);
     mark(c, 3, a.stream);
-    const int64_t pairs = (int64_t)c->plan.stats.n_leaves * c->shape.n_q_heads;
-    const unsigned grid = (unsigned)((pairs + 3) / 4);
-    const HeadScales& out_scale = c->v_scales;
-    const int group = c->shape.n_q_heads / c->shape.n_kv_heads;
-    const int n_leaves = (int)c->plan.stats.n_leaves;
-    if (c->shape.head_dim == 128 && c->out_bf16)
-        hipLaunchKernelGGL((merge_kernel<128, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<bf16_t*>(a.out), a.lse, out_scale, group);
-    else if (c->shape.head_dim == 128)
-        hipLaunchKernelGGL((merge_kernel<128, float>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<float*>(a.out), a.lse, out_scale, group);
-    else if (c->out_bf16)
-        hipLaunchKernelGGL((merge_kernel<64, bf16_t>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<bf16_t*>(a.out), a.lse, out_scale, group);
-    else
-        hipLaunchKernelGGL((merge_kernel<64, float>), dim3(grid), dim3(256), 0, a.stream,
-                           c->d_part_base, n_leaves, c->shape.n_q_heads, a.ws_o, a.ws_ml,
-                           static_cast<float*>(a.out), a.lse, out_scale, group);
+    if (!c->plan.fused) launch_merge(c, a);
     mark(c, 4, a.stream);
     if (c->profile && c->calls_recorded < kMaxProfiledCalls) c->calls_recorded += 1;
     if (!timed) c->profile = was_profiling;
@@ -500,6 +518,10 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
         ctx->opt.wide_rows = -1;
         return ETS_OK;
     }
+    if (!std::strcmp(key, "fuse_merge") && value == -1) {
+        ctx->opt.fuse_merge = -1;
+        return ETS_OK;
+    }
     if (value < 0) return ETS_ERR_INVALID_ARG;
     if (!std::strcmp(key, "stream_chunk")) ctx->opt.stream_chunk = value;
     else if (!std::strcmp(key, "cascade_chunk")) ctx->opt.cascade_chunk = value;
@@ -510,6 +532,7 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value) {
     } else if (!std::strcmp(key, "wave_items")) ctx->opt.wave_items = value;
     else if (!std::strcmp(key, "interleave")) ctx->opt.interleave = value != 0;
     else if (!std::strcmp(key, "wide_rows")) ctx->opt.wide_rows = value;
+    else if (!std::strcmp(key, "fuse_merge")) ctx->opt.fuse_merge = value != 0;
     else if (!std::strcmp(key, "mfma")) ctx->opt.mfma = value;
     else if (!std::strcmp(key, "require_sharing")) ctx->opt.require_sharing = value != 0;
     else if (!std::strcmp(key, "out_bf16")) ctx->out_bf16 = value != 0;

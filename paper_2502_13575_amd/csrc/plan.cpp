@@ -14,6 +14,9 @@
 namespace ets {
 namespace {
 
+// Whether the planner, left to decide, merges inside the attention launch.
+bool fuse_by_default(const ets_stats&) { return false; }
+
 struct Seg {
     int32_t parent_seg = -1;
     int64_t cnt = 0;             // leaf queries at or beneath the segment
@@ -248,10 +251,11 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // t_tile per tile whether it waits on memory (few rows) or computes (many rows)
     const int64_t t_tile = 1500, t_mem = t_tile, kTile = 64;
     auto tile_cost = [&](int64_t) { return t_tile; };
-    // wide kernel: one workgroup per compute unit, about t_wide per 64-token tile of 256 rows
-    // measured: on the 8-heads-per-kv-head shapes the wide kernel gains 5 % on a batch of
-    // searches; with 4 heads per kv head items of 64 rows are as fast
-    const int64_t wide_rows = opt.wide_rows >= 0 ? opt.wide_rows : (G >= 8 ? 64 : 0);
+    // wide kernel: one workgroup per compute unit, about t_wide per 64-token tile of 256 rows.
+    // Off unless asked for: with the launch order merged, items of 64 rows measure 5-6 %
+    // faster on every shape, also with 8 query heads per kv head.  It does not merge, so
+    // a plan that uses it keeps the merge launch.
+    const int64_t wide_rows = opt.wide_rows >= 0 ? opt.wide_rows : 0;
     const int64_t ent_per_wide = std::max<int64_t>(1, kWideRowsPerItem / G);
     const int64_t t_wide = 1500;
     int64_t own_total = 0, work_ns = 0, wide_work_ns = 0;
@@ -514,6 +518,15 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     st.n_cascade_items = (int64_t)p.cascade_items.size();
     st.n_wide_items = (int64_t)p.wide_items.size();
     st.workspace_bytes = st.n_partials * shape.n_q_heads * ((int64_t)shape.head_dim + 2) * 4;
+    // The matrix-core kernel can run the merge itself when it writes every partial and every
+    // leaf query has at least one (the wave that stores a leaf's last partial merges them).
+    // (the merging kernel addresses the workspace with 32-bit byte offsets)
+    bool can_fuse = use_mfma && L > 0 && p.stream_items.empty() && p.wide_items.empty() &&
+                    !p.cascade_items.empty() &&
+                    st.n_partials * shape.n_q_heads * shape.head_dim * 4 < (int64_t(1) << 31);
+    for (int32_t l = 0; can_fuse && l < L; ++l) can_fuse = p.part_base[l + 1] > p.part_base[l];
+    p.fused = can_fuse && (opt.fuse_merge == 1 || (opt.fuse_merge < 0 && fuse_by_default(st)));
+    st.merge_fused = p.fused ? 1 : 0;
     p.valid = true;
     return ETS_OK;
 }
@@ -588,6 +601,12 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
         return idx < (int64_t)p.ent_order.size() ? p.ent_order[(size_t)idx] : 0;
     };
     bad(p.ent_base.size() != p.ent_order.size());
+    // every partial slot has exactly one writer: the merge reads all of a leaf's slots, and the
+    // merge inside the attention launch starts when as many have arrived as the leaf has slots
+    std::vector<char> written((size_t)std::max<int64_t>(p.stats.n_partials, 0), 0);
+    auto writes = [&](int64_t slot) {
+        if (slot < 0 || slot >= (int64_t)written.size() || written[(size_t)slot]++) out.violations += 1;
+    };
     for (size_t i = 0; i < p.cascade_items.size(); ++i) {
         const CascadeItem& it = p.cascade_items[i];
         const bool wave_item = (int64_t)i >= p.n_single;
@@ -630,6 +649,7 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
             const int32_t leaf = p.ent_order[(size_t)(it.ent_begin + e)];
             const int64_t slot = (int64_t)p.part_base[(size_t)leaf] + it.slot_off;
             bad(it.slot_off < 0 || slot >= p.part_base[(size_t)leaf + 1]);
+            writes(slot);
             out.max_partial_row =
                 std::max(out.max_partial_row, slot * shape.n_q_heads + shape.n_q_heads - 1);
         }
@@ -653,6 +673,7 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
             const int32_t leaf = p.ent_order[(size_t)(it.ent_begin + e)];
             const int64_t slot = (int64_t)p.part_base[(size_t)leaf] + it.slot_off;
             bad(it.slot_off < 0 || slot >= p.part_base[(size_t)leaf + 1]);
+            writes(slot);
             out.max_partial_row =
                 std::max(out.max_partial_row, slot * shape.n_q_heads + shape.n_q_heads - 1);
         }
@@ -663,6 +684,7 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
         bad(it.entry < 0 || it.entry >= L);
         if (it.entry >= 0 && it.entry < L)
             bad(it.slot < p.part_base[(size_t)it.entry] || it.slot >= p.part_base[(size_t)it.entry + 1]);
+        writes(it.slot);
         out.max_partial_row = std::max(
             out.max_partial_row, (int64_t)it.slot * shape.n_q_heads + shape.n_q_heads - 1);
         for (int64_t r = it.run_begin; r < it.run_end && r < n_runs; ++r) {
@@ -690,6 +712,13 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
         }
     }
     bad(out.max_partial_row >= p.stats.n_partials * shape.n_q_heads);
+    for (char w : written) bad(w != 1);
+    if (p.fused) {
+        // only the matrix-core kernel's own items count arrivals, and a leaf query without a
+        // partial would never be merged
+        bad(!p.stream_items.empty() || !p.wide_items.empty());
+        for (int64_t l = 0; l < L; ++l) bad(p.part_base[(size_t)l + 1] <= p.part_base[(size_t)l]);
+    }
     return out.violations == 0;
 }
 

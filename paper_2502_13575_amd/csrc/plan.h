@@ -77,10 +77,11 @@ struct PlanOptions {
     int64_t mfma = 1;                // 0 = never use the matrix-core kernel
     int64_t cascade_min_leaves = 2;  // 0 = never use the shared-node kernel
     int64_t wide_rows = -1;          // a shared segment with more query rows than this goes to the
-                                     // wide kernel, 256 rows per item (0 = never; -1 = by the
-                                     // head geometry: 64 with 8 query heads per kv head, else never)
+                                     // wide kernel, 256 rows per item (0 or -1 = never)
     int64_t interleave = 1;          // 1 = workgroups of small items are spread among the others
     int64_t require_sharing = 0;     // 1 = a tree-mode plan that cannot share nodes is refused
+    int64_t fuse_merge = -1;         // merge inside the attention launch: 1 = whenever the plan allows
+                                     // it, 0 = never, -1 = the planner decides
 };
 
 struct Plan {
@@ -114,6 +115,8 @@ struct Plan {
     int32_t adv_room = 0;             // advances the spare runs still hold
     int32_t advances = 0;             // advances applied in place since the plan was built
     int32_t piece = 0;                // longest run the kernels accept (0 = any)
+    bool fused = false;               // the matrix-core kernel merges (no merge launch): every
+                                      // partial comes from it and every leaf query has one
     ets_stats stats{};
 };
 

@@ -56,6 +56,7 @@
 #include <type_traits>
 
 #include "device_utils.hpp"
+#include "merge_kernel.hpp"
 #include "plan.h"
 
 namespace ets {
@@ -227,7 +228,19 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
     lsum += psum;
 }
 
-template <bool FP8>
+// What the merge inside the attention launch needs (instantiations with FUSED only).
+struct MergeTail {
+    const int32_t* part_base;  // [leaf queries + 1] first partial slot of every leaf query
+    int32_t* arrived;          // [leaf queries][kv heads] partial slots stored so far; all
+                               // zero whenever no call is in flight
+    int64_t n_ws_rows;         // partial rows in the workspace; their bytes stay below 2^32
+    void* out;                 // merged output, fp32 or bf16
+    float* lse;
+    int out_bf16;
+    HeadScales v_scales;       // factor of the merged output per kv head
+};
+
+template <bool FP8, bool FUSED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
@@ -235,7 +248,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     int n_single, int n_items,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
     float scale_log2e_base, HeadScales k_scales,
-    float* __restrict__ ws_o, float2* __restrict__ ws_ml) {
+    float* __restrict__ ws_o, float2* __restrict__ ws_ml, MergeTail tail) {
     constexpr int D = 128;
     const int n_kv_heads = (int)gridDim.x;
     constexpr int KROW = kTreeAttnKRow;
@@ -357,6 +370,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // written from there, every store instruction would touch 64 different cache lines
     // with 16 bytes each.  The block goes through a wave-private LDS region (rows padded
     // to 132 floats) instead, and each store instruction writes two whole 512-byte rows.
+    // the workspace as buffer resources, for the device-scope stores of the merging variant
+    const __amdgpu_buffer_rsrc_t rs_ws_o = __builtin_amdgcn_make_buffer_rsrc(
+        ws_o, 0, FUSED ? (int)(uint32_t)(tail.n_ws_rows * D * 4) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_ws_ml = __builtin_amdgcn_make_buffer_rsrc(
+        ws_ml, 0, FUSED ? (int)(uint32_t)(tail.n_ws_rows * 8) : 0, 0x00020000);
     auto store_partial = [&](const f32x4_t (&oacc)[8], float m, float l, int32_t out_row) {
         constexpr int OROW = 132;
         float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
@@ -368,7 +386,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             *reinterpret_cast<float4*>(p + 4) =
                 make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
         }
-        if (b == 0 && r_lane < R) ws_ml[out_row] = make_float2(m * scale_log2e, l);
+        if (b == 0 && r_lane < R) {
+            if constexpr (FUSED)
+                __builtin_amdgcn_raw_buffer_store_b64(
+                    __builtin_bit_cast(u32x2_t, make_float2(m * scale_log2e, l)), rs_ws_ml,
+                    (uint32_t)out_row * 8u, 0, kDeviceScope);
+            else
+                ws_ml[out_row] = make_float2(m * scale_log2e, l);
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const int col = (lane & 31) * 4;
@@ -377,7 +402,67 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             const int r = 2 * k + (lane >> 5);               // row of the block this lane stores
             const int32_t row_out = __shfl(out_row, r, 64);  // lane r holds row r (a = r, b = 0)
             const float4 v = *reinterpret_cast<const float4*>(ob + r * OROW + col);
-            if (16 * blk + r < R) *reinterpret_cast<float4*>(ws_o + (int64_t)row_out * D + col) = v;
+            if (16 * blk + r < R) {
+                if constexpr (FUSED)
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        __builtin_bit_cast(u32x4_t, v), rs_ws_o,
+                        ((uint32_t)row_out * D + (uint32_t)col) * 4u, 0, kDeviceScope);
+                else
+                    *reinterpret_cast<float4*>(ws_o + (int64_t)row_out * D + col) = v;
+            }
+        }
+        if constexpr (FUSED) {
+            // Merge in the same launch: every entry (leaf query) whose rows this wave
+            // has just stored counts one arrival for (leaf query, kv head); the wave that
+            // brings the count to the leaf's number of partial slots merges them.  The
+            // partial rows are stored at device scope and have completed (the wait below)
+            // before the wave counts itself in, and the merging wave reads them at device
+            // scope after its own count has returned, so it sees every slot without any
+            // cache being written back or invalidated as a whole.  It then puts the
+            // counter back to zero for the next call.  Which wave merges depends on
+            // timing; what it computes does not.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            const bool arriver = b == 0 && (a & (G - 1)) == 0 && r_lane < R;
+            int leaf = 0, p0 = 0, np = 0, seen = -2;
+            if (arriver) {
+                leaf = s_ent[e_lane];  // the lane's entry again (not kept over the loop)
+                p0 = tail.part_base[leaf];
+                np = tail.part_base[leaf + 1] - p0;
+                seen = __hip_atomic_fetch_add(tail.arrived + (int64_t)leaf * n_kv_heads + h, 1,
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            uint64_t todo = __ballot(arriver && seen + 1 == np);
+            if (todo != 0) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                const float out_scale = tail.v_scales.s[h];
+                while (todo != 0) {
+                    const int src = __builtin_ctzll(todo);
+                    todo &= todo - 1;
+                    const int m_leaf = __shfl(leaf, src, 64);
+                    const int m_p0 = __shfl(p0, src, 64);
+                    const int m_p1 = m_p0 + __shfl(np, src, 64);
+                    switch (g_shift) {
+                        case 0:
+                            merge_leaf_heads<D, 1, true>(lane, m_leaf, h, m_p0, m_p1, n_q_heads, ws_o,
+                                                   ws_ml, tail.n_ws_rows, tail.out, tail.out_bf16 != 0, tail.lse, out_scale);
+                            break;
+                        case 1:
+                            merge_leaf_heads<D, 2, true>(lane, m_leaf, h, m_p0, m_p1, n_q_heads, ws_o,
+                                                   ws_ml, tail.n_ws_rows, tail.out, tail.out_bf16 != 0, tail.lse, out_scale);
+                            break;
+                        case 2:
+                            merge_leaf_heads<D, 4, true>(lane, m_leaf, h, m_p0, m_p1, n_q_heads, ws_o,
+                                                   ws_ml, tail.n_ws_rows, tail.out, tail.out_bf16 != 0, tail.lse, out_scale);
+                            break;
+                        default:
+                            merge_leaf_heads<D, 8, true>(lane, m_leaf, h, m_p0, m_p1, n_q_heads, ws_o,
+                                                   ws_ml, tail.n_ws_rows, tail.out, tail.out_bf16 != 0, tail.lse, out_scale);
+                            break;
+                    }
+                    if (lane == 0) tail.arrived[(int64_t)m_leaf * n_kv_heads + h] = 0;
+                }
+            }
         }
     };
 

@@ -139,7 +139,8 @@ def test_fuzz_irregular_forests(seed):
     options = {"stream_chunk": [0, 32, 64][seed % 3], "cascade_chunk": [0, 32, 96][(seed // 3) % 3],
                "cascade_rows": [64, 16, 32][(seed // 2) % 3],
                "wave_items": [512, 0, 48, 100000][seed % 4],
-               "wide_rows": [128, 16, 8, 40][(seed // 2) % 4]}
+               "wide_rows": [128, 16, 8, 40][(seed // 2) % 4],
+               "fuse_merge": [0, 1, 1][seed % 3]}
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     for mode in (ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT):
@@ -251,6 +252,7 @@ def test_long_chain_of_one_token_nodes():
 
 
 @pytest.mark.parametrize("name,opts,steps", [("c2_w16", {}, 40), ("c2_w16", {"mfma": 0}, 6),
+                                             ("c2_w16", {"fuse_merge": 1}, 40),
                                              ("c1_tiny", {}, 6), ("c3_pruned", {}, 36)])
 def test_decode_loop_advance_then_append_and_attend_per_layer(name, opts, steps):
     """Decode steps on one plan over two layers' pools, in the order a model has to use:

@@ -286,6 +286,45 @@ def test_plan_check_replays_kernel_accesses_on_configs():
             assert rep.entry_table_entries >= t.n_leaves + 16
 
 
+def test_merge_inside_the_attention_launch_only_when_every_partial_arrives_there():
+    """"fuse_merge" = 1: the plan says so (merge_fused) only when the matrix-core kernel writes
+    every partial result (bf16, head_dim 128, no wide items) and every leaf query has one;
+    in every other case the merge launch stays.  The default is the merge launch."""
+    cfg = CONFIGS["c3_div"]
+    t = make_tree(cfg)
+    for opts, want in (({}, 0), ({"fuse_merge": 1}, 1), ({"fuse_merge": 1, "wide_rows": 16}, 0),
+                       ({"fuse_merge": 1, "mfma": 0}, 0), ({"fuse_merge": 0}, 0),
+                       ({"fuse_merge": 1, "cascade_min_leaves": 0}, 1)):
+        with _ctx(cfg) as ctx:
+            for k, v in opts.items():
+                ctx.set_option(k, v)
+            for mode in (0, 1):
+                st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node, mode)
+                # (a flat plan has no shared segments, hence no wide items)
+                assert st.merge_fused == (want if mode == 0 or "wide_rows" not in opts else 1), (opts, mode)
+                assert ctx.check().violations == 0
+    # a leaf query without a token gets its result from the merge launch
+    parent = np.array([-1, 0, -1], dtype=np.int32)
+    n_tokens = np.array([9, 3, 0], dtype=np.int32)
+    tok_offset = np.array([0, 9, 12], dtype=np.int64)
+    with _ctx(cfg) as ctx:
+        ctx.set_option("fuse_merge", 1)
+        st = ctx.plan(parent, tok_offset, n_tokens, np.array([1, 1, 0], dtype=np.int32))
+        assert st.merge_fused == 1
+        st = ctx.plan(parent, tok_offset, n_tokens, np.array([1, 2, 0], dtype=np.int32))
+        assert st.merge_fused == 0 and ctx.check().violations == 0
+    # shapes the matrix-core kernel does not serve
+    with _ctx((2, 4, 64, ets.ETS_BF16)) as ctx:
+        ctx.set_option("fuse_merge", 1)
+        assert ctx.plan(parent, tok_offset, n_tokens, np.array([1, 0], dtype=np.int32)).merge_fused == 0
+    # the 8-heads-per-kv-head configurations plan no wide items unless asked to
+    t4 = make_tree(CONFIGS["c4_34b"])
+    with _ctx(CONFIGS["c4_34b"]) as ctx:
+        assert ctx.plan(t4.parent, t4.tok_offset, t4.n_tokens, t4.leaf_node).n_wide_items == 0
+        ctx.set_option("wide_rows", 64)
+        assert ctx.plan(t4.parent, t4.tok_offset, t4.n_tokens, t4.leaf_node).n_wide_items > 0
+
+
 def test_plan_check_sweep_of_random_forests():
     """The sweep that once found a wavefront reading entries of the next table (one query
     head per kv head, row blocks past an item's last row): 3000 random forests over the
@@ -307,6 +346,7 @@ def test_plan_check_sweep_of_random_forests():
                 "cascade_min_leaves": int(r.choice([2, 0, 3, 9])),
                 "mfma": int(r.choice([1, 1, 0])),
                 "wide_rows": int(r.choice([128, 0, 16, 40, 300])),
+                "fuse_merge": int(r.choice([0, 1, 1])),
                 "interleave": int(r.choice([1, 0]))}
         mode = int(r.choice([0, 0, 1]))
         if seed % 3 == 0:
