@@ -114,12 +114,12 @@ def measure_config(ets, torch, name, dev, stream, steps=30, flat_steps=3):
             ws = torch.empty(max(st.workspace_bytes, 16), dtype=torch.uint8, device=dev)
             call = 0
 
-            def run(n):
+            def run(n, on=stream):
                 nonlocal call
                 for _ in range(n):
                     p_ = call % n_pools
                     ctx.decode(kd[p_], vd[p_], tree.pool_tokens, qd[p_], out, lse, ws, ws.numel(),
-                               stream.cuda_stream)
+                               on.cuda_stream)
                     call += 1
 
             run(3)
@@ -133,6 +133,25 @@ def measure_config(ets, torch, name, dev, stream, steps=30, flat_steps=3):
                 res["speedup_tree_vs_flat"] = round(us / res["us_per_layer"], 2)
                 res["flat_over_unique_bytes"] = round(st.flat_kv_bytes / max(st.unique_kv_bytes, 1), 2)
                 continue
+            # The same calls replayed from a HIP graph (a decode step of 32 layers captured
+            # once): what is left when the host's launch work is off the path.  The calls
+            # allocate nothing, wait for nothing and clear nothing with a memset.
+            n_cap = min(n_pools, 32)
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()  # capture needs a stream of its own
+            call = 0
+            with torch.cuda.graph(graph, stream=side):
+                run(n_cap, side)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            reps = max(3, n_steps // n_cap)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                graph.replay()
+            torch.cuda.synchronize()
+            graph_us = (time.perf_counter() - t0) / (reps * n_cap) * 1e6
+            del graph
             ctx.set_option("profile", 1)
             ctx.profile_read()
             run(n_steps)
@@ -150,6 +169,7 @@ def measure_config(ets, torch, name, dev, stream, steps=30, flat_steps=3):
                 "wide_items": int(st.n_wide_items),
                 "wide_kernel_us": round(pr.wide_ms / max(pr.calls, 1) * 1e3, 2) if st.n_wide_items > 0 else 0.0,
                 "us_per_layer": round(us, 1),
+                "graph_replay_us_per_layer": round(graph_us, 1),
                 "leaf_queries_per_s": round(L / (us * 1e-6), 1),
                 "unique_kv_GBps": round(st.unique_kv_bytes / (us * 1e-6) / 1e9, 1),
                 "unique_kv_frac_of_hbm_peak": round(st.unique_kv_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
