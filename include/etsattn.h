@@ -61,13 +61,14 @@ typedef enum { ETS_F32 = 0, ETS_BF16 = 1 } ets_dtype;
  * 1/sqrt(head_dim).
  *
  * Which shapes get the method.  Reading every shared node once per call for all the
- * leaves beneath it is built for bfloat16 pools with head_dim 128 (the shapes of the
- * paper's models).  Every other accepted shape -- fp32 pools, which exist as a correctness
- * path, and head_dim 64 -- gives the same result through the per-leaf kernel: every leaf
- * query reads its whole chain itself (shared rows come out of the caches, not out of the
- * plan), at the cost of the flat baseline.  ets_stats.shares_nodes says which of the two a
- * plan is, and with the option "require_sharing" ets_plan refuses (ETS_ERR_UNSUPPORTED) a
- * tree-mode plan that would not share. */
+ * leaves beneath it is built for bfloat16 pools, head_dim 128 (the shapes of the paper's
+ * models) and head_dim 64.  fp32 pools exist as a correctness path: they give the same
+ * result through the per-leaf kernel, in which every leaf query reads its whole chain
+ * itself (shared rows come out of the caches, not out of the plan), at the cost of the
+ * flat baseline.  ets_stats.shares_nodes says which of the two a plan is, and with the
+ * option "require_sharing" ets_plan refuses (ETS_ERR_UNSUPPORTED) a tree-mode plan that
+ * would not share.  Pools of E4M3 codes, the wide kernel and step prefill are built for
+ * head_dim 128 only. */
 typedef struct {
     int32_t n_kv_heads;
     int32_t n_q_heads;
@@ -118,8 +119,8 @@ typedef struct {
     int64_t workspace_bytes; /* device scratch ets_tree_decode_attn needs                */
     int64_t cascade_tokens;  /* unique tokens read (once) by the shared-node kernel      */
     int64_t stream_tokens;   /* tokens read by the streaming kernel, repeats included    */
-    int64_t shares_nodes;    /* 1: shared nodes are read once per call (bf16, head_dim   */
-                             /* 128, tree mode); 0: every leaf reads its chain itself    */
+    int64_t shares_nodes;    /* 1: shared nodes are read once per call (bf16 pools, tree */
+                             /* mode); 0: every leaf reads its chain itself              */
     int64_t n_wide_items;    /* work items of the kernel for widely shared segments      */
     int64_t wide_tokens;     /* unique tokens of those segments (part of cascade_tokens) */
     int64_t merge_fused;     /* 1: the shared-node kernel merges the partials itself (no  */
@@ -240,13 +241,13 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *                    items
  *   "wide_rows"      a shared segment with more query rows than this is read by the
  *                    wide kernel (256 query rows per work item, bound by the matrix
- *                    cores) instead of by several items of "cascade_rows" rows each
+ *                    cores; head_dim 128) instead of by several items of "cascade_rows" rows each
  *                    (0 or -1 = never, the default: items of 64 rows in the merged launch
  *                    order measure 5-6 % faster on every configuration tried)
  *   "fuse_merge"     1 = the shared-node kernel also merges: the wavefront that stores a
  *                    leaf query's last partial result combines them, and no merge kernel
  *                    is launched.  Only for plans whose partial results all come from
- *                    that kernel (bf16 or E4M3 pools with head_dim 128, no wide items),
+ *                    that kernel (bf16 or E4M3 pools, no wide items),
  *                    in which every leaf query has a token, and whose workspace is below
  *                    2 GiB; other plans keep the merge launch (ets_stats.merge_fused
  *                    tells).  Same results bit for bit.  The arrival counters belong to
@@ -260,12 +261,12 @@ ets_status ets_plan_append_rows(const ets_ctx* ctx, int64_t* rows);
  *                    tokens is walked by a single wavefront, four such items to
  *                    a workgroup (default 512; 0 = every item gets a workgroup)
  *   "require_sharing"  1 = ets_plan in tree mode returns ETS_ERR_UNSUPPORTED when this
- *                    context cannot read shared nodes once (shape other than bf16 /
- *                    head_dim 128, or "mfma" / "cascade_min_leaves" set to 0) instead
+ *                    context cannot read shared nodes once (fp32 pools, or "mfma" /
+ *                    "cascade_min_leaves" set to 0) instead
  *                    of falling back to per-leaf reads; 0 (default) = fall back
- *   "mfma"           1 (default) = matrix-core kernel for bf16 pools with
- *                    head_dim 128; 0 = vector-ALU kernel for every shape (each
- *                    leaf then reads its whole chain itself)
+ *   "mfma"           1 (default) = matrix-core kernel for bf16 pools; 0 = vector-ALU
+ *                    kernel for every shape (each leaf then reads its whole chain
+ *                    itself)
  *   "out_bf16"       1 = ets_tree_decode_attn writes `out` as bfloat16 (the merged fp32
  *                    result rounded to nearest even), for a consumer that takes the next
  *                    projection's input in bf16; 0 (default) = fp32.  Effective from

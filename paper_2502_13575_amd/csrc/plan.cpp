@@ -238,7 +238,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // result per query and query head (written, then read by the merge); otherwise
     // every query reads the segment itself as part of its own item.  A segment is
     // shared when the KV bytes this saves exceed the partial bytes it adds.
-    const bool use_mfma = opt.mfma != 0 && shape.dtype == ETS_BF16 && shape.head_dim == 128;
+    const bool use_mfma = opt.mfma != 0 && shape.dtype == ETS_BF16;  // head_dim 64 or 128
     const bool cascade_ok = mode == ETS_PLAN_TREE && use_mfma && opt.cascade_min_leaves > 0;
     if (mode == ETS_PLAN_TREE && opt.require_sharing && !cascade_ok) return ETS_ERR_UNSUPPORTED;
     st.shares_nodes = cascade_ok ? 1 : 0;
@@ -255,7 +255,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     // Off unless asked for: with the launch order merged, items of 64 rows measure 5-6 %
     // faster on every shape, also with 8 query heads per kv head.  It does not merge, so
     // a plan that uses it keeps the merge launch.
-    const int64_t wide_rows = opt.wide_rows >= 0 ? opt.wide_rows : 0;
+    const int64_t wide_rows = opt.wide_rows >= 0 && shape.head_dim == 128 ? opt.wide_rows : 0;
     const int64_t ent_per_wide = std::max<int64_t>(1, kWideRowsPerItem / G);
     const int64_t t_wide = 1500;
     int64_t own_total = 0, work_ns = 0, wide_work_ns = 0;

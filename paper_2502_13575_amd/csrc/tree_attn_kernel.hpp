@@ -48,6 +48,9 @@
 // fetches the same 8 elements with an 8-byte load, and the codes are widened to bf16
 // (exactly: 4 significant bits) when the tile is staged; everything after the staging
 // is the bf16 path unchanged.
+// head_dim 64 (template parameter D; bf16 pools): rows of 128 bytes = 8 pieces of 16, two
+// score products and four output fragments per 16 tokens; for the V transposition two
+// neighbouring lanes fetch the same piece and take one half of it each.
 // Loads of the next tile are in flight while the current one is computed.
 // The result per query row is the unnormalised partial (o, m, l), m in log2
 // units, merged later along each leaf's chain.
@@ -110,31 +113,44 @@ __device__ __forceinline__ std::conditional_t<FP8, u32x2_t, u32x4_t> load_row_pi
 static_assert(kTreeAttnRowsPerItem == 64, "4 waves x 16 rows");
 constexpr int kTreeAttnKRow = 17;         // 16-byte units per padded K row in LDS (272 bytes)
 
+// Geometry by head_dim D (128 or 64): a K row in LDS is D / 8 16-byte units plus one of
+// padding; the score product contracts over D in D / 32 matrix instructions; the output
+// has D / 16 blocks of 16 rows of V^T (fragments).
+template <int D>
+constexpr int k_row_units() {
+    return D / 8 + 1;
+}
+static_assert(k_row_units<128>() == kTreeAttnKRow, "the step-prefill kernel stages K the same way");
+
 // One step of a row-parallel item: 32 staged tokens (V already fp16) against one block
 // of 16 query rows.
+template <int D>
 __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
                                           const u32x4_t* __restrict__ vs_lane, int b, int n_valid,
-                                          const bf16x8_t (&qf)[4], f32x4_t (&oacc)[8], float& m,
-                                          float& lsum, float scale_log2e, float raise_margin) {
-    constexpr int KROW = kTreeAttnKRow;
+                                          const bf16x8_t (&qf)[D / 32], f32x4_t (&oacc)[D / 16],
+                                          float& m, float& lsum, float scale_log2e,
+                                          float raise_margin) {
+    constexpr int KROW = k_row_units<D>();
+    constexpr int NKK = D / 32, NX = D / 16, HX = NX / 2;
     // scores S^T = K Q^T
     f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     // one accumulator after the other: consecutive matrix instructions that accumulate
     // into the same registers issue twice as fast as alternating ones
-    for (int kk = 0; kk < 4; ++kk)
+    for (int kk = 0; kk < NKK; ++kk)
         s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[4 * kk]), qf[kk], s0, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+    for (int kk = 0; kk < NKK; ++kk)
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[16 * KROW + 4 * kk]), qf[kk],
                                                      s1, 0, 0, 0);
-    // The first four V^T fragments are requested from LDS before the softmax arithmetic, so
-    // that they arrive while it runs; the other four follow behind the first matrix
-    // instructions.  (Left to itself the compiler reads each fragment just ahead of its use.)
-    u32x4_t vf[4];
+    // The first half of the V^T fragments is requested from LDS before the softmax
+    // arithmetic, so that they arrive while it runs; the other half follows behind the first
+    // matrix instructions.  (Left to itself the compiler reads each fragment just ahead of
+    // its use.)
+    u32x4_t vf[HX];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) vf[x] = vs_lane[x * 64];
+    for (int x = 0; x < HX; ++x) vf[x] = vs_lane[x * 64];
     __builtin_amdgcn_sched_barrier(0);
     // lane holds row a of the block, tokens 4 b + i (first half) and 16 + 4 b + i (second half)
     float s[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
@@ -153,7 +169,7 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
         const float alpha = fast_exp2((m - m_new) * scale_log2e);
         lsum *= alpha;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) oacc[x] *= alpha;
+        for (int x = 0; x < NX; ++x) oacc[x] *= alpha;
         m = m_new;
     }
     const float mc = m * scale_log2e;
@@ -167,14 +183,14 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
+    for (int x = 0; x < HX; ++x) {
         oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vf[x]), pf, oacc[x], 0, 0, 0);
-        vf[x] = vs_lane[(4 + x) * 64];
+        vf[x] = vs_lane[(HX + x) * 64];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int x = 0; x < 4; ++x)
-        oacc[4 + x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vf[x]), pf, oacc[4 + x], 0, 0, 0);
+    for (int x = 0; x < HX; ++x)
+        oacc[HX + x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(vf[x]), pf, oacc[HX + x], 0, 0, 0);
     lsum += psum;
 }
 
@@ -183,14 +199,16 @@ __device__ __forceinline__ void attn_step(const u32x4_t* __restrict__ ks_lane,
 // region.  The weight enters the P V product as a bf16 head in contraction slots
 // 0..3 and its bf16 remainder in slots 4..7, against the same four V rows in both
 // slot halves, so one MFMA per fragment applies both.
+template <int D>
 __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_lane,
                                                const u32x2_t* __restrict__ vs_lane, int b,
-                                               int n_valid, const bf16x8_t (&qf)[4],
-                                               f32x4_t (&oacc)[8], float& m, float& lsum,
+                                               int n_valid, const bf16x8_t (&qf)[D / 32],
+                                               f32x4_t (&oacc)[D / 16], float& m, float& lsum,
                                                float scale_log2e, float raise_margin) {
+    constexpr int NKK = D / 32, NX = D / 16;
     f32x4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+    for (int kk = 0; kk < NKK; ++kk)
         s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ks_lane[4 * kk]), qf[kk], s, 0, 0, 0);
     // lane holds row a, tokens 4 b + i; masking is unconditional so that the scores are
     // consumed in straight-line code after the matrix instructions
@@ -205,7 +223,7 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
         const float alpha = fast_exp2((m - m_new) * scale_log2e);
         lsum *= alpha;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) oacc[x] *= alpha;
+        for (int x = 0; x < NX; ++x) oacc[x] *= alpha;
         m = m_new;
     }
     const float mc = m * scale_log2e;
@@ -220,7 +238,7 @@ __device__ __forceinline__ void attn_half_step(const u32x4_t* __restrict__ ks_la
         pf[4 + i] = (__bf16)(p - (float)hi);
     }
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
+    for (int x = 0; x < NX; ++x) {
         const u32x2_t t = vs_lane[x * 64];
         const u32x4_t vf = {t[0], t[1], t[0], t[1]};
         oacc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vf), pf, oacc[x], 0, 0, 0);
@@ -240,7 +258,7 @@ struct MergeTail {
     HeadScales v_scales;       // factor of the merged output per kv head
 };
 
-template <bool FP8, bool FUSED>
+template <bool FP8, bool FUSED, int D = 128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
@@ -249,11 +267,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
     float scale_log2e_base, HeadScales k_scales,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml, MergeTail tail) {
-    constexpr int D = 128;
+    static_assert(D == 128 || D == 64, "head_dim");
     const int n_kv_heads = (int)gridDim.x;
-    constexpr int KROW = kTreeAttnKRow;
+    constexpr int KROW = k_row_units<D>();
+    constexpr int NKK = D / 32;            // matrix instructions of a score product
+    constexpr int NX = D / 16;             // V^T fragments (blocks of 16 output elements)
+    constexpr int PPR = D / 8;             // 16-byte pieces (8 elements) per row
+    constexpr int RPL = 64 / PPR;          // K rows one load instruction of a wave covers
+    constexpr int NKL = 16 / RPL;          // K loads per 16 tokens
     constexpr int KS_UNITS = 64 * KROW;    // K tile: 64 padded rows
-    constexpr int VS_UNITS = 2 * 8 * 64;   // V^T fragments: [step][x][lane]
+    constexpr int VS_UNITS = 2 * NX * 64;  // V^T fragments: [step][x][lane]
     // K tile, then V^T fragments; the K part is reused for the token-parallel fold
     __shared__ u32x4_t smem[KS_UNITS + VS_UNITS];
     __shared__ float sm_m[4][16];
@@ -297,13 +320,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const float raise_margin = 8.0f / scale_log2e;  // raw-score distance of 2^8 in weight
 
     // wave w fetches half hw of step 2 tile + sw of every tile
-    std::conditional_t<FP8, u32x2_t, u32x4_t> kraw[4], vraw[4];
+    std::conditional_t<FP8, u32x2_t, u32x4_t> kraw[NKL], vraw[4];
     constexpr uint32_t stride_b = FP8 ? D : D * 2;  // bytes between the tokens of a head plane
     constexpr uint32_t piece_b = FP8 ? 8 : 16;      // bytes of a lane's 8 elements
     const int64_t plane = (int64_t)h * pool_tokens;  // first row of this kv head
-    // K: token 16 hw + 4 i + b;  V: contraction slot 4 hw + j of group b = token 16 hw + 4 b + j
-    const uint32_t k_lane_off = (uint32_t)(16 * hw + b) * stride_b + a * piece_b;
-    const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + a * piece_b;
+    // K: a load covers RPL consecutive rows, the lane's piece pa of row rb: token
+    // 16 hw + RPL i + rb (head_dim 128: pa = a, rb = b).
+    // V: contraction slot 4 hw + j of group b = token 16 hw + 4 b + j.  With head_dim 128
+    // the lane's piece is a, of which it transposes all 8 elements; with head_dim 64 a row
+    // has 8 pieces, lanes 2 p and 2 p + 1 both fetch piece p and transpose one half each
+    // (output element 4 a + x of fragment x).
+    const int pa = lane & (PPR - 1), rb = lane / PPR;
+    const int va = D == 128 ? a : a >> 1;
+    const uint32_t k_lane_off = (uint32_t)(16 * hw + rb) * stride_b + pa * piece_b;
+    const uint32_t v_lane_off = (uint32_t)(16 * hw + 4 * b) * stride_b + va * piece_b;
     // Buffer loads: a step's rows are addressed through a descriptor that covers exactly
     // the step (base = its first row at this kv head, size = n rows), so a load is a
     // scalar descriptor plus a 32-bit lane offset, and rows past the end of a ragged step
@@ -321,15 +351,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                 // full step: every row is in range; the row stepping rides in the scalar offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = load_row_piece<FP8>(kr, k_lane_off, 4 * i * (int)stride_b, aux_tag);
+                    if (i < NKL)
+                        kraw[i] = load_row_piece<FP8>(kr, k_lane_off, RPL * i * (int)stride_b, aux_tag);
                     vraw[i] = load_row_piece<FP8>(vr, v_lane_off, i * (int)stride_b, aux_tag);
                 }
             } else {
                 // ragged step: the whole offset is in the range-checked lane offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = load_row_piece<FP8>(kr, k_lane_off + (uint32_t)(4 * i) * stride_b, 0,
-                                                  aux_tag);
+                    if (i < NKL)
+                        kraw[i] = load_row_piece<FP8>(kr, k_lane_off + (uint32_t)(RPL * i) * stride_b,
+                                                      0, aux_tag);
                     vraw[i] = load_row_piece<FP8>(vr, v_lane_off + (uint32_t)i * stride_b, 0,
                                                   aux_tag);
                 }
@@ -366,25 +398,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     }
     const int rr = r_lane;  // rows past R belong to padding entries: read, never written
 
-    // Partial result of the wave's block.  Lane (a, b) holds row a, d = 32 b + 8 i + x:
-    // written from there, every store instruction would touch 64 different cache lines
-    // with 16 bytes each.  The block goes through a wave-private LDS region (rows padded
-    // to 132 floats) instead, and each store instruction writes two whole 512-byte rows.
+    // Partial result of the wave's block.  Lane (a, b) holds row a, d = 32 b + 8 i + x
+    // (head_dim 64: d = 16 b + 4 i + x): written from there, every store instruction would
+    // touch 64 different cache lines with 16 bytes each.  The block goes through a
+    // wave-private LDS region (rows padded by 4 floats) instead, and each store
+    // instruction writes whole rows (two of 512 bytes, or four of 256).
     // the workspace as buffer resources, for the device-scope stores of the merging variant
     const __amdgpu_buffer_rsrc_t rs_ws_o = __builtin_amdgcn_make_buffer_rsrc(
         ws_o, 0, FUSED ? (int)(uint32_t)(tail.n_ws_rows * D * 4) : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_ws_ml = __builtin_amdgcn_make_buffer_rsrc(
         ws_ml, 0, FUSED ? (int)(uint32_t)(tail.n_ws_rows * 8) : 0, 0x00020000);
-    auto store_partial = [&](const f32x4_t (&oacc)[8], float m, float l, int32_t out_row) {
-        constexpr int OROW = 132;
+    auto store_partial = [&](const f32x4_t (&oacc)[NX], float m, float l, int32_t out_row) {
+        constexpr int OROW = D + 4;
         float* ob = reinterpret_cast<float*>(smem) + w * (16 * OROW);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float* p = ob + a * OROW + 32 * b + 8 * i;
+            float* p = ob + a * OROW + (D / 4) * b + (D / 16) * i;
             *reinterpret_cast<float4*>(p) =
                 make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
-            *reinterpret_cast<float4*>(p + 4) =
-                make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
+            if constexpr (D == 128)
+                *reinterpret_cast<float4*>(p + 4) =
+                    make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
         }
         if (b == 0 && r_lane < R) {
             if constexpr (FUSED)
@@ -396,10 +430,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        const int col = (lane & 31) * 4;
+        constexpr int LPR = D / 4;       // lanes that store a row, 16 bytes each
+        constexpr int RPS = 64 / LPR;    // rows per store instruction
+        const int col = (lane & (LPR - 1)) * 4;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int r = 2 * k + (lane >> 5);               // row of the block this lane stores
+        for (int k = 0; k < 16 / RPS; ++k) {
+            const int r = RPS * k + lane / LPR;              // row of the block this lane stores
             const int32_t row_out = __shfl(out_row, r, 64);  // lane r holds row r (a = r, b = 0)
             const float4 v = *reinterpret_cast<const float4*>(ob + r * OROW + col);
             if (16 * blk + r < R) {
@@ -466,13 +502,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         }
     };
 
+    // A wave's own 16 tokens into its private LDS region (small and token-parallel items):
+    // K rows as they are, V as bf16 transposed pieces (two tokens per dword).
+    auto stage_private = [&](u32x4_t* ksw, u32x2_t* vsw) {
+#pragma unroll
+        for (int i = 0; i < NKL; ++i) ksw[(RPL * i + rb) * KROW + pa] = widen_raw(kraw[i]);
+        const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
+                               widen_raw(vraw[3])};
+        if constexpr (D == 128) {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+                u32x2_t t;
+                t[0] = __builtin_amdgcn_perm(vw[1][x >> 1], vw[0][x >> 1], sel);
+                t[1] = __builtin_amdgcn_perm(vw[3][x >> 1], vw[2][x >> 1], sel);
+                vsw[x * 64 + lane] = t;
+            }
+        } else {
+            // the lane's half of the piece: elements 4 (a & 1) + x, x = 0..3
+            uint32_t hv[4][2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                hv[i][0] = (a & 1) ? vw[i][2] : vw[i][0];
+                hv[i][1] = (a & 1) ? vw[i][3] : vw[i][1];
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+                u32x2_t t;
+                t[0] = __builtin_amdgcn_perm(hv[1][x >> 1], hv[0][x >> 1], sel);
+                t[1] = __builtin_amdgcn_perm(hv[3][x >> 1], hv[2][x >> 1], sel);
+                vsw[x * 64 + lane] = t;
+            }
+        }
+    };
+
     if (wave_item) {
         // ---- A small item walked by this wave alone: 16-token units in order (unit u =
         // half u & 1 of step u >> 1) through the wave's own LDS region, next unit's loads
         // in flight while the current one is computed; no fold, no workgroup barrier.
-        const uint32_t k_off0 = (uint32_t)b * stride_b + a * piece_b;        // K row b (+ 4 i)
-        const uint32_t v_off0 = (uint32_t)(4 * b) * stride_b + a * piece_b;  // V row 4 b (+ i)
-        u32x4_t* ksw = smem + w * (16 * KROW + 256);
+        const uint32_t k_off0 = (uint32_t)rb * stride_b + pa * piece_b;       // K row rb (+ RPL i)
+        const uint32_t v_off0 = (uint32_t)(4 * b) * stride_b + va * piece_b;  // V row 4 b (+ i)
+        u32x4_t* ksw = smem + w * (16 * KROW + NX * 32);
         u32x2_t* vsw = reinterpret_cast<u32x2_t*>(ksw + 16 * KROW);
         auto unit_rows = [&](int u, int64_t& tok) {
             const Run sd = my_steps[u >> 1];  // uniform: scalar load
@@ -490,28 +561,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                     __builtin_amdgcn_make_buffer_rsrc(vb, 0, n * (int)stride_b, 0x00020000);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kraw[i] = load_row_piece<FP8>(kr, k_off0 + (uint32_t)(4 * i) * stride_b, 0,
-                                                  std::integral_constant<int, 2>{});
+                    if (i < NKL)
+                        kraw[i] = load_row_piece<FP8>(kr, k_off0 + (uint32_t)(RPL * i) * stride_b, 0,
+                                                      std::integral_constant<int, 2>{});
                     vraw[i] = load_row_piece<FP8>(vr, v_off0 + (uint32_t)i * stride_b, 0,
                                                   std::integral_constant<int, 2>{});
                 }
             }
         };
         auto stage_own = [&](int n) {
-            if (n > 0) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = widen_raw(kraw[i]);
-                const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
-                                       widen_raw(vraw[3])};
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-                    u32x2_t t;
-                    t[0] = __builtin_amdgcn_perm(vw[1][x >> 1], vw[0][x >> 1], sel);
-                    t[1] = __builtin_amdgcn_perm(vw[3][x >> 1], vw[2][x >> 1], sel);
-                    vsw[x * 64 + lane] = t;
-                }
-            }
+            if (n > 0) stage_private(ksw, vsw);
         };
         const int n_units = 2 * n_steps;
         int64_t tok = 0;
@@ -519,14 +578,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         issue_unit(tok, n_cur);
         const int head = h * G + (rr & (G - 1));
         const bf16_t* qp = q + ((int64_t)ent * n_q_heads + head) * D;
-        bf16x8_t qf[4];
+        bf16x8_t qf[NKK];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
+        for (int kk = 0; kk < NKK; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
         const int32_t out_row = (ent_slot + it.slot_off) * n_q_heads + head;
-        f32x4_t oacc[8];
+        f32x4_t oacc[NX];
         float m = -INFINITY, lsum = 0.f;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) oacc[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int x = 0; x < NX; ++x) oacc[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         stage_own(n_cur);
         __builtin_amdgcn_s_waitcnt(0);  // nothing issued so far may count against the loop's waits
         for (int u = 0; u < n_units; ++u) {
@@ -534,8 +593,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             const int n_next = u + 1 < n_units ? unit_rows(u + 1, tok_next) : 0;
             issue_unit(tok_next, n_next);
             if (n_cur > 0)
-                attn_half_step(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
-                               scale_log2e, raise_margin);
+                attn_half_step<D>(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
+                                  scale_log2e, raise_margin);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             stage_own(n_next);
@@ -564,21 +623,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     // Q rows as B operands: lane (column a = query row, group b) holds
     // q[row][32 kk + 8 b .. + 8) for kk = 0..3.  The workspace row of the lane's
     // partial result is looked up here as well, off the critical path.
-    bf16x8_t qf[4];
+    bf16x8_t qf[NKK];
     int32_t out_row;
     {
         const int head = h * G + (rr & (G - 1));
         const bf16_t* qp = q + ((int64_t)ent * n_q_heads + head) * D;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
+        for (int kk = 0; kk < NKK; ++kk) qf[kk] = as_bf16x8(load16(qp + 32 * kk + 8 * b));
         out_row = (ent_slot + it.slot_off) * n_q_heads + head;
     }
     if ((int)threadIdx.x < n_steps) sm_desc[threadIdx.x] = desc_raw;
 
-    f32x4_t oacc[8];
+    f32x4_t oacc[NX];
     float m = -INFINITY, lsum = 0.f;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) oacc[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int x = 0; x < NX; ++x) oacc[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     auto read_desc = [&](int sidx) {
         Run sd{0, 0, 0};
@@ -594,27 +653,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     auto stage = [&](const Run& sd) {
         if (sd.n > 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                ks[(32 * sw + 16 * hw + 4 * i + b) * KROW + a] = widen_raw(kraw[i]);
+            for (int i = 0; i < NKL; ++i)
+                ks[(32 * sw + 16 * hw + RPL * i + rb) * KROW + pa] = widen_raw(kraw[i]);
             const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
                                    widen_raw(vraw[3])};
             // This half's four contraction slots of every V^T fragment (8 of its 16
             // bytes), converted to fp16 for the P V product once for all row blocks:
-            // element x of the lane's 16-byte piece, tokens 4 b .. 4 b + 3.
+            // element x of the lane's 16-byte piece (head_dim 64: of the lane's half of
+            // it), tokens 4 b .. 4 b + 3.
             u32x2_t* vs2 = reinterpret_cast<u32x2_t*>(vs);
+            uint32_t dw[4][NX / 2];  // the dwords (two elements each) this lane transposes
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (D == 128) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dw[i][j] = vw[i][j];
+                } else {
+                    dw[i][0] = (a & 1) ? vw[i][2] : vw[i][0];
+                    dw[i][1] = (a & 1) ? vw[i][3] : vw[i][1];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NX / 2; ++j) {
                 u32x2_t te, to;
                 te[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_lo(vw[0][j]), bf16_lo(vw[1][j])));
+                                                         bf16_lo(dw[0][j]), bf16_lo(dw[1][j])));
                 te[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_lo(vw[2][j]), bf16_lo(vw[3][j])));
+                                                         bf16_lo(dw[2][j]), bf16_lo(dw[3][j])));
                 to[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_hi(vw[0][j]), bf16_hi(vw[1][j])));
+                                                         bf16_hi(dw[0][j]), bf16_hi(dw[1][j])));
                 to[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(
-                                                         bf16_hi(vw[2][j]), bf16_hi(vw[3][j])));
-                vs2[((sw * 8 + 2 * j) * 64 + lane) * 2 + hw] = te;
-                vs2[((sw * 8 + 2 * j + 1) * 64 + lane) * 2 + hw] = to;
+                                                         bf16_hi(dw[2][j]), bf16_hi(dw[3][j])));
+                vs2[((sw * NX + 2 * j) * 64 + lane) * 2 + hw] = te;
+                vs2[((sw * NX + 2 * j + 1) * 64 + lane) * 2 + hw] = to;
             }
         }
     };
@@ -641,8 +712,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
                     if (sidx >= n_steps) break;
                     const int n_valid = __builtin_amdgcn_readfirstlane(sm_desc[sidx][2]);
                     if (n_valid > 0)  // an empty spare step was never staged
-                        attn_step(ks + (32 * st + a) * KROW + b, vs + st * 8 * 64 + lane, b,
-                                        n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
+                        attn_step<D>(ks + (32 * st + a) * KROW + b, vs + st * NX * 64 + lane, b,
+                                     n_valid, qf, oacc, m, lsum, scale_log2e, raise_margin);
                 }
             }
 
@@ -660,22 +731,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         // Token parallel: every wave walks its own 16-token units (half hw of step
         // 2 tile + sw) through a private LDS region; no workgroup barrier in the loop.
         u32x4_t* ksw = ks + 16 * w * KROW;
-        u32x2_t* vsw = reinterpret_cast<u32x2_t*>(vs) + w * (8 * 64);
+        u32x2_t* vsw = reinterpret_cast<u32x2_t*>(vs) + w * (NX * 64);
         auto stage_unit = [&](const Run& sd) {
-            if (sd.n > 16 * hw) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) ksw[(4 * i + b) * KROW + a] = widen_raw(kraw[i]);
-                const u32x4_t vw[4] = {widen_raw(vraw[0]), widen_raw(vraw[1]), widen_raw(vraw[2]),
-                                       widen_raw(vraw[3])};
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-                    u32x2_t t;
-                    t[0] = __builtin_amdgcn_perm(vw[1][x >> 1], vw[0][x >> 1], sel);
-                    t[1] = __builtin_amdgcn_perm(vw[3][x >> 1], vw[2][x >> 1], sel);
-                    vsw[x * 64 + lane] = t;
-                }
-            }
+            if (sd.n > 16 * hw) stage_private(ksw, vsw);
         };
         stage_unit(sd_loaded);
         __builtin_amdgcn_s_waitcnt(0);
@@ -686,8 +744,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             sd_loaded = read_desc(2 * (tile + 1) + sw);
             issue_loads(sd_loaded, std::integral_constant<int, 2>{});
             if (n_cur > 0)
-                attn_half_step(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
-                               scale_log2e, raise_margin);
+                attn_half_step<D>(ksw + a * KROW + b, vsw + lane, b, n_cur, qf, oacc, m, lsum,
+                                  scale_log2e, raise_margin);
             // the wave's LDS accesses complete in order; keep the compiler from moving them
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -714,7 +772,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         f32x4_t* fold = reinterpret_cast<f32x4_t*>(smem) + lane;
         if (w != 0) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) fold[((w - 1) * 8 + x) * 64] = oacc[x] * f_own;
+            for (int x = 0; x < NX; ++x) fold[((w - 1) * NX + x) * 64] = oacc[x] * f_own;
         }
         __syncthreads();
         if (w != 0) return;
@@ -724,8 +782,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
             l += sm_l[k][a] * fast_exp2((sm_m[k][a] - ms) * scale_log2e);
         m = ms;
 #pragma unroll
-        for (int x = 0; x < 8; ++x)
-            oacc[x] = oacc[x] * f_own + fold[x * 64] + fold[(8 + x) * 64] + fold[(16 + x) * 64];
+        for (int x = 0; x < NX; ++x)
+            oacc[x] = oacc[x] * f_own + fold[x * 64] + fold[(NX + x) * 64] + fold[(2 * NX + x) * 64];
     }
 
     if (rowpar ? !computes : w != 0) return;

@@ -67,6 +67,29 @@ def test_configs_full_parity(name, variant):
         assert st.cascade_tokens == 0
 
 
+@pytest.mark.parametrize("name,heads", [("c2_w16", (8, 32)), ("c3_div", (8, 32)), ("c3_pruned", (4, 32)),
+                                        ("c3_div", (2, 2)), ("c2_w16", (4, 8))])
+@pytest.mark.parametrize("options", [{}, {"wave_items": 0, "interleave": 0}, {"fuse_merge": 1},
+                                     {"cascade_rows": 16, "cascade_chunk": 96}])
+def test_head_dim_64_full_parity(name, heads, options):
+    """bf16 pools with head_dim 64 go through the matrix-core kernel as well (half as many
+    16-byte pieces per row, half as many score and output blocks): shared nodes are read
+    once, for 1, 2, 4 and 8 query heads per kv head, in all three kinds of work item."""
+    cfg = dataclasses.replace(CONFIGS[name], n_kv_heads=heads[0], n_q_heads=heads[1], head_dim=64)
+    tree = make_tree(cfg)
+    k, v, q = make_values_host(cfg, tree)
+    print("case d64", name, heads, options, flush=True)
+    with make_ctx(cfg, options) as ctx:
+        out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
+        assert ctx.check().violations == 0
+    assert st.shares_nodes == 1 and st.n_cascade_items > 0 and st.n_stream_items == 0
+    assert st.cascade_tokens > 0 and st.merge_fused == options.get("fuse_merge", 0)
+    oo, ol = oracle_full(cfg, tree, k, v, q)
+    err = compare(out.cpu().numpy().reshape(-1, 64), lse.cpu().numpy().reshape(-1),
+                  oo.reshape(-1, 64), ol.reshape(-1), "bf16", "d64 " + name)
+    assert err["out_abs"] <= 2e-4 and err["lse_abs"] <= 1e-4, err
+
+
 @pytest.mark.parametrize("variant", ["tree", "flat"])
 def test_c4_sampled_parity(variant):
     cfg = CONFIGS["c4_34b"]
@@ -253,6 +276,7 @@ def test_long_chain_of_one_token_nodes():
 
 @pytest.mark.parametrize("name,opts,steps", [("c2_w16", {}, 40), ("c2_w16", {"mfma": 0}, 6),
                                              ("c2_w16", {"fuse_merge": 1}, 40),
+                                             ("c2_w16", {"head_dim": 64}, 40),
                                              ("c1_tiny", {}, 6), ("c3_pruned", {}, 36)])
 def test_decode_loop_advance_then_append_and_attend_per_layer(name, opts, steps):
     """Decode steps on one plan over two layers' pools, in the order a model has to use:
@@ -262,6 +286,9 @@ def test_decode_loop_advance_then_append_and_attend_per_layer(name, opts, steps)
     the re-plan, and both pools end up bitwise equal to the oracle's."""
     from workload import with_growth_room, make_new_tokens_host
     cfg = CONFIGS[name]
+    opts = dict(opts)
+    if "head_dim" in opts:
+        cfg = dataclasses.replace(cfg, head_dim=opts.pop("head_dim"))
     tree = with_growth_room(make_tree(cfg), steps + 2)
     n_layers = 2
     host = [make_values_host(dataclasses.replace(cfg, seed=cfg.seed + 17 * l), tree)

@@ -313,8 +313,11 @@ def test_merge_inside_the_attention_launch_only_when_every_partial_arrives_there
         assert st.merge_fused == 1
         st = ctx.plan(parent, tok_offset, n_tokens, np.array([1, 2, 0], dtype=np.int32))
         assert st.merge_fused == 0 and ctx.check().violations == 0
-    # shapes the matrix-core kernel does not serve
+    # head_dim 64 is served by the matrix-core kernel as well, fp32 pools are not
     with _ctx((2, 4, 64, ets.ETS_BF16)) as ctx:
+        ctx.set_option("fuse_merge", 1)
+        assert ctx.plan(parent, tok_offset, n_tokens, np.array([1, 0], dtype=np.int32)).merge_fused == 1
+    with _ctx((2, 4, 64, ets.ETS_F32)) as ctx:
         ctx.set_option("fuse_merge", 1)
         assert ctx.plan(parent, tok_offset, n_tokens, np.array([1, 0], dtype=np.int32)).merge_fused == 0
     # the 8-heads-per-kv-head configurations plan no wide items unless asked to
@@ -369,11 +372,11 @@ def test_plan_check_sweep_of_random_forests():
 
 
 def test_shapes_without_node_sharing_say_so_or_refuse():
-    """Shared nodes are read once only for bf16 pools with head_dim 128.  Other accepted
-    shapes fall back to per-leaf reads and report it (shares_nodes 0, nothing on the
-    shared-node kernel); with "require_sharing" the tree-mode plan is refused instead."""
+    """Shared nodes are read once for bf16 pools (head_dim 128 or 64).  fp32 pools fall back
+    to per-leaf reads and report it (shares_nodes 0, nothing on the shared-node kernel);
+    with "require_sharing" the tree-mode plan is refused instead."""
     t = make_tree(CONFIGS["c2_w16"])
-    for shape, shares in [((8, 32, 128, ets.ETS_BF16), 1), ((8, 32, 64, ets.ETS_BF16), 0),
+    for shape, shares in [((8, 32, 128, ets.ETS_BF16), 1), ((8, 32, 64, ets.ETS_BF16), 1),
                           ((8, 32, 128, ets.ETS_F32), 0), ((1, 2, 64, ets.ETS_F32), 0)]:
         with _ctx(shape) as ctx:
             st = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
