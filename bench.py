@@ -194,6 +194,10 @@ def main():
                     help="CPU time budget of the oracle baseline sample (0 = skip)")
     ap.add_argument("--flat-steps", type=int, default=2, help="timed steps of the flat baseline (0 = skip)")
     ap.add_argument("--option", action="append", default=[], help="planner knob key=value")
+    ap.add_argument("--head-dim", type=int, default=0, choices=[0, 64, 128],
+                    help="run the configuration's tree with this head_dim instead of its own "
+                         "(64: the shared-node kernel's other instantiation; the E4M3, prefill "
+                         "and selection legs need 128 and are skipped)")
     ap.add_argument("--decode-tokens", type=int, default=8,
                     help="decode tokens of the append/advance measurement on one extra pool (0 = skip)")
     ap.add_argument("--prefill-layers", type=int, default=4,
@@ -237,6 +241,10 @@ def main():
     ets.load_library()          # fails loudly if the HIP library is not built
     dev = "cuda:0"
     cfg = CONFIGS[args.config]
+    if args.head_dim and args.head_dim != cfg.head_dim:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name="%s_d%d" % (cfg.name, args.head_dim),
+                                  head_dim=args.head_dim)
     tree = make_tree(cfg)
     dt = ets.ETS_F32 if cfg.dtype == "f32" else ets.ETS_BF16
     ctx = ets.Context(cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, dt, 0)

@@ -62,15 +62,17 @@ def _chain_tokens(tree):
     return tot
 
 
-@pytest.mark.parametrize("heads", [(4, 4), (4, 8), (2, 8), (2, 16), (8, 64)])
+@pytest.mark.parametrize("heads", [(4, 4), (4, 8), (2, 8), (2, 16), (8, 64), (2, 8, 64), (1, 8, 64),
+                                   (4, 4, 64)])
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_fused_merge_every_head_grouping_on_irregular_forests(heads, seed):
     """1, 2, 4 and 8 query heads per kv head (the merging wave's lane layout differs for
-    each), forests with interior leaf queries, duplicates, ragged, empty and one-token
+    each) and both head sizes, forests with interior leaf queries, duplicates, ragged, empty and one-token
     nodes.  A leaf query whose chain holds no token gets its result (out = 0, lse = -inf)
     from the merge launch and nothing arrives for it, so such a plan keeps the launch."""
-    hkv, hq = heads
-    cfg = TreeConfig("fz", hkv, hq, 128, "bf16", 0, 0, 0, 0, 0, None, seed=700 + seed)
+    hkv, hq = heads[:2]
+    d = heads[2] if len(heads) > 2 else 128
+    cfg = TreeConfig("fz", hkv, hq, d, "bf16", 0, 0, 0, 0, 0, None, seed=700 + seed)
     tree = random_tree(40 + 7 * seed + hq, n_nodes=[30, 90, 160][seed], n_leaves=[9, 40, 70][seed],
                        max_tokens=[90, 40, 12][seed], p_empty=[0.0, 0.05, 0.15][seed])
     k, v, q = make_values_host(cfg, tree)
@@ -80,8 +82,8 @@ def test_fused_merge_every_head_grouping_on_irregular_forests(heads, seed):
     for out, lse in fused:
         assert torch.equal(out, out0) and torch.equal(lse, lse0)
     oo, ol = oracle_full(cfg, tree, k, v, q)
-    compare(out0.cpu().numpy().reshape(-1, 128), lse0.cpu().numpy().reshape(-1),
-            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "forest")
+    compare(out0.cpu().numpy().reshape(-1, d), lse0.cpu().numpy().reshape(-1),
+            oo.reshape(-1, d), ol.reshape(-1), "bf16", "forest")
 
 
 def test_fused_merge_with_bf16_output_and_e4m3_pools():
