@@ -67,8 +67,7 @@ typedef enum { ETS_F32 = 0, ETS_BF16 = 1 } ets_dtype;
  * itself (shared rows come out of the caches, not out of the plan), at the cost of the
  * flat baseline.  ets_stats.shares_nodes says which of the two a plan is, and with the
  * option "require_sharing" ets_plan refuses (ETS_ERR_UNSUPPORTED) a tree-mode plan that
- * would not share.  Pools of E4M3 codes, the wide kernel and step prefill are built for
- * head_dim 128 only. */
+ * would not share.  The wide kernel and step prefill are built for head_dim 128 only. */
 typedef struct {
     int32_t n_kv_heads;
     int32_t n_q_heads;
@@ -285,7 +284,7 @@ ets_status ets_set_option(ets_ctx* ctx, const char* key, int64_t value);
  *                        K[t,h,d] = k_scale * value(k_code),  V[t,h,d] = v_scale * value(v_code)
  *                    with one positive finite scale per pool.  Layout, row numbering and
  *                    alignment are as for native pools with 1-byte elements; q stays
- *                    bf16.  Only for bf16 contexts with head_dim 128 (ETS_ERR_UNSUPPORTED
+ *                    bf16.  Only for bf16 contexts (ETS_ERR_UNSUPPORTED
  *                    otherwise) and with the "mfma" option on (else ets_tree_decode_attn
  *                    returns ETS_ERR_UNSUPPORTED).  ets_kv_append then copies 1-byte
  *                    elements (k_new, v_new hold codes); step prefill reads such pools

@@ -289,11 +289,12 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     for (int64_t y0 = 0; y0 < n_wgs; y0 += 65535) {
         const unsigned ny = (unsigned)std::min<int64_t>(65535, n_wgs - y0);
         const bool fp8 = c->kv_format == ETS_KV_FP8_E4M3;
-        // head_dim 64 exists for bf16 pools only (E4M3 pools need head_dim 128)
-        auto kernel = c->shape.head_dim == 64
-                          ? (c->plan.fused ? tree_attn_kernel<false, true, 64> : tree_attn_kernel<false, false, 64>)
-                      : c->plan.fused ? (fp8 ? tree_attn_kernel<true, true> : tree_attn_kernel<false, true>)
-                                      : (fp8 ? tree_attn_kernel<true, false> : tree_attn_kernel<false, false>);
+        auto kernel =
+            c->shape.head_dim == 64
+                ? (c->plan.fused ? (fp8 ? tree_attn_kernel<true, true, 64> : tree_attn_kernel<false, true, 64>)
+                                 : (fp8 ? tree_attn_kernel<true, false, 64> : tree_attn_kernel<false, false, 64>))
+                : (c->plan.fused ? (fp8 ? tree_attn_kernel<true, true> : tree_attn_kernel<false, true>)
+                                 : (fp8 ? tree_attn_kernel<true, false> : tree_attn_kernel<false, false>));
         hipLaunchKernelGGL(kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0, a.stream,
                            a.k, a.v, a.pool_tokens, static_cast<const bf16_t*>(a.q), c->d_runs,
                            c->d_cascade, c->d_wg_map, (int)y0, (int)n_single, (int)n_items,
@@ -554,7 +555,7 @@ ets_status ets_set_kv_format(ets_ctx* ctx, int kv_format, float k_scale, float v
         if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) ||
             !std::isfinite(v_scale))
             return ETS_ERR_INVALID_ARG;
-        if (ctx->shape.dtype != ETS_BF16 || ctx->shape.head_dim != 128) return ETS_ERR_UNSUPPORTED;
+        if (ctx->shape.dtype != ETS_BF16) return ETS_ERR_UNSUPPORTED;
     }
     ctx->kv_format = kv_format;
     for (int h = 0; h < kMaxScaledHeads; ++h) {

@@ -48,7 +48,7 @@
 // fetches the same 8 elements with an 8-byte load, and the codes are widened to bf16
 // (exactly: 4 significant bits) when the tile is staged; everything after the staging
 // is the bf16 path unchanged.
-// head_dim 64 (template parameter D; bf16 pools): rows of 128 bytes = 8 pieces of 16, two
+// head_dim 64 (template parameter D; either pool format): rows of 8 pieces of 8 elements, two
 // score products and four output fragments per 16 tokens; for the V transposition two
 // neighbouring lanes fetch the same piece and take one half of it each.
 // Loads of the next tile are in flight while the current one is computed.

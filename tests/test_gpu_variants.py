@@ -53,6 +53,28 @@ def test_fp8kv_full_parity(name, mode):
             oo.reshape(-1, 128), ol.reshape(-1), "bf16", "fp8 %s/mode%d" % (name, mode))
 
 
+@pytest.mark.parametrize("name,heads,options", [("c3_div", (8, 32), {}), ("c3_pruned", (4, 32), {"fuse_merge": 1}),
+                                                ("c2_w16", (2, 2), {"wave_items": 0}),
+                                                ("c2_w16", (4, 8), {"cascade_rows": 16})])
+def test_fp8kv_head_dim_64_full_parity(name, heads, options):
+    """Pools of E4M3 codes with head_dim 64 (rows of 64 bytes, 8-byte pieces) through the
+    shared-node kernel's instantiation for that head size, with per-head scales."""
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS[name], n_kv_heads=heads[0], n_q_heads=heads[1], head_dim=64)
+    tree = make_tree(cfg)
+    kc, vc, q = make_values_fp8_host(cfg, tree, KS, VS)
+    print("case fp8 d64", name, heads, options, flush=True)
+    with make_ctx(cfg, options) as ctx:
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, KS, VS)
+        out, lse, st = run(ctx, tree, pool_to_device(kc), pool_to_device(vc), to_device(q))
+        assert ctx.check().violations == 0
+    assert st.shares_nodes == 1 and st.n_stream_items == 0
+    assert st.unique_kv_bytes == st.unique_tokens * 2 * cfg.n_kv_heads * 64
+    oo, ol = oracle_fp8(cfg, tree, kc, vc, q)
+    compare(out.cpu().numpy().reshape(-1, 64), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, 64), ol.reshape(-1), "bf16", "fp8 d64 " + name)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_fp8kv_fuzz_irregular_forests(seed):
     """Ragged steps, empty nodes, several roots, duplicated and interior leaf queries, every

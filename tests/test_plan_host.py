@@ -482,10 +482,18 @@ def test_kv_format_host_logic():
         assert 2 * pf1.unique_kv_bytes == pf2.unique_kv_bytes
         assert 2 * pf1.streamed_kv_bytes == pf2.streamed_kv_bytes
         assert (pf1.n_items, pf1.n_runs, pf1.flops) == (pf2.n_items, pf2.n_runs, pf2.flops)
-    for shape in [(2, 4, 64, ets.ETS_BF16), (2, 4, 128, ets.ETS_F32)]:
+    for shape in [(2, 4, 64, ets.ETS_F32), (2, 4, 128, ets.ETS_F32)]:
         with _ctx(shape) as ctx:
             with pytest.raises(ets.EtsError) as e:
                 ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, 1.0, 1.0)
             assert e.value.status == 4
             ctx.set_kv_format(ets.ETS_KV_NATIVE)
             ctx.set_option("out_bf16", 1)
+    # bf16 contexts of either head size take pools of codes (step prefill: head_dim 128 only)
+    with _ctx((2, 4, 64, ets.ETS_BF16)) as ctx:
+        ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, 1.0, 1.0)
+        st64 = ctx.plan(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert st64.unique_kv_bytes == st64.unique_tokens * 2 * 2 * 64 and st64.shares_nodes == 1
+        with pytest.raises(ets.EtsError) as e:
+            ctx.plan_prefill(t.parent, t.tok_offset, t.n_tokens, t.leaf_node)
+        assert e.value.status == 4
