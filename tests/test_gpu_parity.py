@@ -209,8 +209,9 @@ def test_repeated_runs_bitwise_equal_on_ragged_paths(share):
                 oo.reshape(-1, 128), ol.reshape(-1), "bf16", "one node, n=%d" % n)
 
 
-def test_edge_cases_empty_and_duplicate_leaves():
-    cfg = TreeConfig("edge", 1, 4, 128, "bf16", 0, 0, 0, 0, 0, None, seed=77)
+@pytest.mark.parametrize("d", [128, 64])
+def test_edge_cases_empty_and_duplicate_leaves(d):
+    cfg = TreeConfig("edge", 1, 4, d, "bf16", 0, 0, 0, 0, 0, None, seed=77)
     parent = np.array([-1, 0, -1, 2], np.int32)
     n_tok = np.array([0, 5, 0, 0], np.int32)
     off = np.array([0, 0, 0, 0], np.int64)
@@ -222,8 +223,8 @@ def test_edge_cases_empty_and_duplicate_leaves():
     oo, ol = oracle_full(cfg, tree, k, v, q)
     with make_ctx(cfg) as ctx:
         out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
-        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "edge")
+        compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, d), ol.reshape(-1), "bf16", "edge")
         assert torch.equal(out[0], out[1]) and torch.equal(lse[0], lse[1])
         assert torch.all(out[2] == 0) and torch.all(lse[2] == float("-inf"))
         # no leaves at all: the call is a no-op
@@ -256,7 +257,8 @@ def test_device_error_paths():
         assert torch.all(out == 0) and torch.all(lse == 0)   # outputs untouched on error
 
 
-def test_long_chain_of_one_token_nodes():
+@pytest.mark.parametrize("d", [128, 64])
+def test_long_chain_of_one_token_nodes(d):
     n = 1500
     parent = np.arange(-1, n - 1, dtype=np.int32)
     n_tok = np.ones(n, np.int32)
@@ -264,14 +266,14 @@ def test_long_chain_of_one_token_nodes():
     leaf = np.array([n - 1, n - 1, 700], np.int32)
     from workload import Tree
     tree = Tree(parent, off, n_tok, leaf, n)
-    cfg = TreeConfig("chain", 2, 8, 128, "bf16", 0, 0, 0, 0, 0, None, seed=31)
+    cfg = TreeConfig("chain", 2, 8, d, "bf16", 0, 0, 0, 0, 0, None, seed=31)
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     print("case one-token chain", flush=True)
     with make_ctx(cfg) as ctx:
         out, lse, st = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
-    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "chain")
+    compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, d), ol.reshape(-1), "bf16", "chain")
 
 
 @pytest.mark.parametrize("name,opts,steps", [("c2_w16", {}, 40), ("c2_w16", {"mfma": 0}, 6),
@@ -461,7 +463,8 @@ def test_decode_and_prefill_under_graph_capture():
         del g
 
 
-def test_row_blocks_past_an_items_last_row():
+@pytest.mark.parametrize("d", [128, 64])
+def test_row_blocks_past_an_items_last_row(d):
     """Regression: an item with 17..48 query rows and one query head per kv head leaves
     whole 16-row blocks of its workgroup without rows; their waves still look up entries
     (up to 63 past the item's first) and fetch the query rows those name, so the entry
@@ -478,14 +481,14 @@ def test_row_blocks_past_an_items_last_row():
                "wave_items": int(r.choice([512, 0, 48, 100000])),
                "cascade_min_leaves": int(r.choice([2, 2, 0, 3]))}
     assert tree.n_leaves == 47
-    cfg = TreeConfig("pad", 2, 2, 128, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
+    cfg = TreeConfig("pad", 2, 2, d, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
     k, v, q = make_values_host(cfg, tree)
     oo, ol = oracle_full(cfg, tree, k, v, q)
     print("case entry padding", options, flush=True)
     with make_ctx(cfg, options) as ctx:
         out, lse, _ = gpu_attn(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q))
-    compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-            oo.reshape(-1, 128), ol.reshape(-1), "bf16", "entry padding")
+    compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+            oo.reshape(-1, d), ol.reshape(-1), "bf16", "entry padding")
     # one head per kv head, 17..48 leaves under one node, few entries in all
     for n_leaves in (17, 24, 33, 48):
         parent = np.array([-1] + [0] * n_leaves, np.int32)
@@ -497,8 +500,8 @@ def test_row_blocks_past_an_items_last_row():
         oo, ol = oracle_full(cfg, t2, k, v, q)
         with make_ctx(cfg) as ctx:
             out, lse, _ = gpu_attn(ctx, t2, pool_to_device(k), pool_to_device(v), to_device(q))
-        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "entry padding %d" % n_leaves)
+        compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, d), ol.reshape(-1), "bf16", "entry padding %d" % n_leaves)
 
 
 def test_kv_append_needs_room_only_behind_growing_nodes():
