@@ -263,16 +263,18 @@ def test_fp8kv_prefill_c3_sampled_and_decode_on_one_context():
 
 
 def test_wide_random_sweep():
-    """Two hundred random forests (1..160 nodes, 1..100 leaf queries, every group size,
-    random planner knobs, both pool formats; every third one also step prefill), every
-    output row against the oracle.  Cheap on the GPU, and wide enough to hit layouts the
+    """Two hundred random forests (1..160 nodes, 1..100 leaf queries, every group size, both
+    head sizes, random planner knobs incl. the merge inside the attention launch, both pool
+    formats; every third one of head_dim 128 also step prefill), every output row against
+    the oracle.  Cheap on the GPU, and wide enough to hit layouts the
     hand-made cases miss (it found the entry-table padding and the append room check)."""
     from workload import make_prefill_queries_host
     shapes = [(2, 8), (1, 1), (2, 16), (4, 8), (1, 2), (8, 32), (3, 12), (2, 2), (1, 8), (4, 4)]
     for seed in range(5000, 5200):
         r = np.random.default_rng(seed)
         hkv, hq = shapes[seed % len(shapes)]
-        cfg = TreeConfig("sweep", hkv, hq, 128, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
+        d = 64 if (seed // 10) % 2 else 128
+        cfg = TreeConfig("sweep", hkv, hq, d, "bf16", 0, 0, 0, 0, 0, None, seed=seed)
         tree = random_tree(seed, n_nodes=int(r.integers(2, 160)), n_leaves=int(r.integers(1, 100)),
                            max_tokens=int(r.choice([5, 20, 40, 90, 200, 500])),
                            p_root=float(r.choice([0.02, 0.1, 0.3])),
@@ -283,24 +285,25 @@ def test_wide_random_sweep():
                    "wave_items": int(r.choice([512, 0, 48, 100000])),
                    "cascade_min_leaves": int(r.choice([2, 2, 0, 3])),
                    "wide_rows": int(r.choice([128, 16, 4, 40, 0])),
-                   "interleave": int(r.choice([1, 1, 0]))}
+                   "interleave": int(r.choice([1, 1, 0])),
+                   "fuse_merge": int(r.choice([0, 0, 1]))}
         mode = int(r.choice([ets.ETS_PLAN_TREE, ets.ETS_PLAN_TREE, ets.ETS_PLAN_FLAT]))
         print("case sweep", seed, (hkv, hq), tree.n_nodes, tree.n_leaves, options, mode, flush=True)
         k, v, q = make_values_host(cfg, tree)
         oo, ol = oracle_full(cfg, tree, k, v, q)
         with make_ctx(cfg, options) as ctx:
             out, lse, _ = run(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(q), mode)
-        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-                oo.reshape(-1, 128), ol.reshape(-1), "bf16", "sweep %d" % seed)
+        compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                oo.reshape(-1, d), ol.reshape(-1), "bf16", "sweep %d" % seed)
         ks, vs = float(r.choice([1.0, KS, 0.5])), float(r.choice([1.0, VS, 3.0]))
         kc, vc, q8 = make_values_fp8_host(cfg, tree, ks, vs)
         fo, fl = oracle_fp8(cfg, tree, kc, vc, q8, ks, vs)
         with make_ctx(cfg, options) as ctx:
             ctx.set_kv_format(ets.ETS_KV_FP8_E4M3, ks, vs)
             out, lse, _ = run(ctx, tree, pool_to_device(kc), pool_to_device(vc), to_device(q8), mode)
-        compare(out.cpu().numpy().reshape(-1, 128), lse.cpu().numpy().reshape(-1),
-                fo.reshape(-1, 128), fl.reshape(-1), "bf16", "sweep e4m3 %d" % seed)
-        if seed % 3 == 0 and 0 < int(tree.n_tokens[tree.leaf_node].sum()) < 3000:
+        compare(out.cpu().numpy().reshape(-1, d), lse.cpu().numpy().reshape(-1),
+                fo.reshape(-1, d), fl.reshape(-1), "bf16", "sweep e4m3 %d" % seed)
+        if d == 128 and seed % 3 == 0 and 0 < int(tree.n_tokens[tree.leaf_node].sum()) < 3000:
             qs = make_prefill_queries_host(cfg, tree)
             with make_ctx(cfg) as ctx:
                 po, pl, st = gpu_prefill(ctx, tree, pool_to_device(k), pool_to_device(v), to_device(qs))
