@@ -90,8 +90,32 @@ __device__ __forceinline__ void merge_leaf_heads(int lane, int64_t leaf, int h, 
     const int j0 = h * G;
     const int64_t stride = (int64_t)n_q_heads * D;  // floats between slots
 
-    float ms = -INFINITY;  // per head lane % G
-    for (int c0 = p0; c0 < p1; c0 += LPH) {
+    // Loads are issued as early as their addresses are known, and a batch of rows at a time:
+    // the first round's (m, l) pairs and the first batch of rows go out together, before
+    // anything is reduced (a leaf rarely has more partials than one round holds), so that a
+    // typical leaf costs two or three memory round trips.
+    // rows in flight per lane and batch (inside the attention kernel registers are scarce)
+    constexpr int UNROLL = COHERENT && EPL >= 8 ? 2 : 4;
+    const int g_row = lane / LPH;
+    auto load_rows = [&](Piece (&v)[UNROLL][EPL / VEC], int64_t base, int k, int cn) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            if (k + u < cn) {  // uniform
+#pragma unroll
+                for (int c = 0; c < EPL / VEC; ++c)
+                    v[u][c] = load_piece(base + (k + u) * stride + c * VEC);
+            }
+        }
+    };
+    const int cn0 = min(LPH, p1 - p0);
+    const int64_t base0 = ((int64_t)p0 * n_q_heads + j0) * D + lane * EPL;  // in floats
+    float2 ml0 = make_float2(-INFINITY, 0.f);
+    if (p0 + k_ml < p1) ml0 = load_ml((int64_t)(p0 + k_ml) * n_q_heads + j0 + g_ml);
+    Piece v0[UNROLL][EPL / VEC];
+    load_rows(v0, base0, 0, cn0);
+
+    float ms = strided_max<G>(ml0.x);  // per head lane % G
+    for (int c0 = p0 + LPH; c0 < p1; c0 += LPH) {
         const int p = c0 + k_ml;
         const float mv = p < p1 ? load_ml((int64_t)p * n_q_heads + j0 + g_ml).x : -INFINITY;
         ms = fmaxf(ms, strided_max<G>(mv));
@@ -101,12 +125,11 @@ __device__ __forceinline__ void merge_leaf_heads(int lane, int64_t leaf, int h, 
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
     float ls = 0.f;  // per head lane % G
-    const int g_row = lane / LPH;
     for (int c0 = p0; c0 < p1; c0 += LPH) {
         const int p = c0 + k_ml;
         float wv = 0.f, lw = 0.f;
         if (p < p1) {
-            const float2 ml = load_ml((int64_t)p * n_q_heads + j0 + g_ml);
+            const float2 ml = c0 == p0 ? ml0 : load_ml((int64_t)p * n_q_heads + j0 + g_ml);
             wv = fast_exp2(ml.x - ms);
             lw = ml.y * wv;
         }
@@ -120,24 +143,19 @@ __device__ __forceinline__ void merge_leaf_heads(int lane, int64_t leaf, int h, 
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[c * VEC + i] = fmaf(v[c].f[i], w, acc[c * VEC + i]);
         };
-        constexpr int UNROLL = EPL >= 16 ? 2 : 4;  // rows in flight per lane
         int k = 0;
-        for (; k + UNROLL <= cn; k += UNROLL) {
-            Piece v[UNROLL][EPL / VEC];
+        if (c0 == p0) {  // the batch that is already here
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                for (int c = 0; c < EPL / VEC; ++c)
-                    v[u][c] = load_piece(base + (k + u) * stride + c * VEC);
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) accumulate(k + u, v[u]);
+                if (u < cn) accumulate(u, v0[u]);
+            k = UNROLL;
         }
-        for (; k < cn; ++k) {
-            Piece v[EPL / VEC];
+        for (; k < cn; k += UNROLL) {
+            Piece v[UNROLL][EPL / VEC];
+            load_rows(v, base, k, cn);
 #pragma unroll
-            for (int c = 0; c < EPL / VEC; ++c)
-                v[c] = load_piece(base + k * stride + c * VEC);
-            accumulate(k, v);
+            for (int u = 0; u < UNROLL; ++u)
+                if (k + u < cn) accumulate(k + u, v[u]);
         }
     }
     const bool empty = p1 == p0;
