@@ -247,9 +247,12 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     auto grow_end_of = [&](int32_t node) { return p.tok_offset[node] + p.n_tokens[node]; };
     const int64_t partial_bytes = 2 * (int64_t)shape.n_q_heads * (shape.head_dim + 2) * 4;
     const int64_t ent_per_item = std::max<int64_t>(1, opt.cascade_rows / G);
-    // cost model in nanoseconds per tile of 64 tokens: a workgroup needs about
-    // t_tile per tile whether it waits on memory (few rows) or computes (many rows)
-    const int64_t t_tile = 1500, t_mem = t_tile, kTile = 64;
+    // cost model in nanoseconds: a resident workgroup needs about t_tile per tile of 64
+    // tokens whether it waits on memory (few rows) or computes (many rows), and t_item to
+    // start and to store its partial results; 768 workgroups are resident (three per
+    // compute unit).  Measured: 2.1-2.7 us per tile, 6.5-8.5 us per item; the sum predicts the
+    // attention launch of the configurations within 5 %.
+    const int64_t t_tile = 2500, t_mem = t_tile, t_item = 7000, kTile = 64, kResident = 768;
     auto tile_cost = [&](int64_t) { return t_tile; };
     // wide kernel: one workgroup per compute unit, about t_wide per 64-token tile of 256 rows.
     // Off unless asked for: with the launch order merged, items of 64 rows measure 5-6 %
@@ -259,6 +262,7 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
     const int64_t ent_per_wide = std::max<int64_t>(1, kWideRowsPerItem / G);
     const int64_t t_wide = 1500;
     int64_t own_total = 0, work_ns = 0, wide_work_ns = 0;
+    int64_t items_est = L;  // one item per leaf query for what it reads itself, plus:
     for (Seg& sg : segs) {
         sg.cascade = cascade_ok && sg.cnt >= 2 && sg.cnt >= opt.cascade_min_leaves &&
                      sg.tokens > 0 &&
@@ -274,9 +278,11 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
                             shape.n_kv_heads;
         } else if (sg.cascade) {
             st.cascade_tokens += sg.tokens;
-            for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item)
+            for (int64_t e0 = 0; e0 < sg.cnt; e0 += ent_per_item) {
                 work_ns += ceil_div(sg.tokens, kTile) *
                            tile_cost(std::min(ent_per_item, sg.cnt - e0) * G) * shape.n_kv_heads;
+                items_est += 1;
+            }
         } else {
             st.stream_tokens += sg.tokens * sg.cnt;
             own_total += sg.tokens * sg.cnt;
@@ -284,12 +290,20 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         }
     }
     // time the whole call is expected to take: the larger of the HBM time of the
-    // unique bytes (at ~5.5 TB/s) and the modelled work spread over 1024 resident
-    // workgroups; no single item should take more than a third of it
+    // unique bytes (at ~5.5 TB/s) and the modelled work spread over the resident
+    // workgroups; no single item should take more than half of it: finer items balance no
+    // better (the launch order starts the long ones first) and every further chunk of a
+    // shared segment costs one more partial result for each leaf query beneath it
+    // (measured on the configurations: the optimum lies at 45-55 % of the call time)
     // (1-byte pools are budgeted like 2-byte ones: their launch is bound by the number
     // of loads, not by their bytes, and finer items would only add partial results)
     const int64_t hbm_ns = st.unique_kv_bytes * (esz < 2 ? 2 : 1) / 5500;
-    const int64_t item_budget_ns = std::max<int64_t>(std::max(hbm_ns, work_ns / 1024) / 3, 4 * t_mem);
+    // (plus the start and the end of the items on the critical path, which is what a small
+    // call mostly consists of)
+    const int64_t call_ns =
+        std::max(hbm_ns, (work_ns + items_est * t_item * shape.n_kv_heads) / kResident) +
+        2 * t_item;
+    const int64_t item_budget_ns = std::max<int64_t>(call_ns / 2, 4 * t_mem);
 
     // wide items: no longer than a quarter of the time their launch is expected to take on
     // 256 compute units, and not so short that start-up dominates
