@@ -1,7 +1,8 @@
 // Decode-step advance on the device: between two tokens of one search step the tree's
 // topology is fixed (ETS paper, Sec. 4.1) and only the nodes that hold leaf queries grow.
 //   advance_runs_kernel  extends, in the step lists the attention kernels read, the tail
-//                        of every copy of every growing node by one row;
+//                        of every copy of every growing node by one row
+//                        (refresh_units_kernel then updates the start table's copies);
 //   kv_append_kernel     writes the new token's K and V row of every growing node into
 //                        the pools.
 #pragma once
@@ -24,6 +25,24 @@ __global__ void advance_runs_kernel(Run* __restrict__ runs, const AdvEntry* __re
         Run* spare = runs + e.r_spare;
         if (spare->n == 0) spare->tok = e.end0 + advances;
         spare->n += 1;
+    }
+}
+
+// Launched behind advance_runs_kernel, one thread per listed slot: the attention kernel's
+// start table holds copies of every item's first two steps, which follow the step lists.
+__global__ void refresh_units_kernel(UnitSlot* __restrict__ units, const int32_t* __restrict__ slots,
+                                     int n_slots, const Run* __restrict__ runs) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_slots) return;
+    const int slot = slots[i];
+    UnitSlot* u = units + slot;
+    const CascadeItem item = u->item;
+    for (int j = 0; j < 2; ++j) {
+        const int k = unit_step_index(item, slot & 3, j);
+        if (k < 0 || item.run_begin + k >= item.run_end) continue;
+        const Run r = runs[item.run_begin + k];
+        if (j == 0) u->first = r;
+        else u->second = r;
     }
 }
 

@@ -36,14 +36,14 @@ struct ets_ctx {
     size_t d_cap = 0;
     Run* d_runs = nullptr;
     StreamItem* d_stream = nullptr;
-    CascadeItem* d_cascade = nullptr;
+    UnitSlot* d_units = nullptr;     // the matrix-core kernel's start table, in launch order
     CascadeItem* d_wide = nullptr;
-    int32_t* d_wg_map = nullptr;     // launch order of the matrix-core kernel
     int32_t* d_ent_order = nullptr;
     int32_t* d_part_base = nullptr;
     int32_t* d_ent_base = nullptr;   // part_base of ent_order[i]
     AdvEntry* d_adv = nullptr;       // decode-step advance: tails to extend
     int32_t* d_adv_src = nullptr;    // per growing node: leaf query that supplies its new token
+    int32_t* d_adv_slots = nullptr;  // slots of the start table to refresh after an advance
     int64_t* d_adv_last_row = nullptr;  // per growing node: newest pool row at plan time
     int32_t* d_arrived = nullptr;    // merge inside the attention launch: [leaf][kv head] counters
     // step prefill: its own plan and device tables
@@ -133,9 +133,8 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const Plan& p = c->plan;
     const size_t b_runs = align_up(p.runs.size() * sizeof(Run), 256);
     const size_t b_stream = align_up(p.stream_items.size() * sizeof(StreamItem), 256);
-    const size_t b_casc = align_up(p.cascade_items.size() * sizeof(CascadeItem), 256);
+    const size_t b_units = align_up(p.units.size() * sizeof(UnitSlot), 256);
     const size_t b_wide = align_up(p.wide_items.size() * sizeof(CascadeItem), 256);
-    const size_t b_map = align_up(p.wg_map.size() * sizeof(int32_t), 256);
     // Both per-entry tables end in kEntryPadding zero entries (leaf query 0, slot 0): a
     // wave's 16-entry scalar load may run past the item's last entry (check_plan replays
     // how far).
@@ -144,13 +143,14 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t b_base = align_up(p.part_base.size() * sizeof(int32_t), 256);
     const size_t b_adv = align_up(p.adv.size() * sizeof(AdvEntry), 256);
     const size_t b_asrc = align_up(p.adv_src.size() * sizeof(int32_t), 256);
+    const size_t b_aslot = align_up(p.adv_slots.size() * sizeof(int32_t), 256);
     const size_t b_arow = align_up(p.adv_last_row.size() * sizeof(int64_t), 256);
     // arrival counters of the merge inside the attention launch: zero here, and put back
     // to zero by the kernel itself at the end of every call
     const size_t b_arrived =
         p.fused ? align_up((size_t)p.stats.n_leaves * c->shape.n_kv_heads * sizeof(int32_t), 256) : 0;
-    const size_t total = b_runs + b_stream + b_casc + b_wide + b_map + 2 * b_ent + b_base + b_adv +
-                         b_asrc + b_arow + b_arrived + 256;
+    const size_t total = b_runs + b_stream + b_units + b_wide + 2 * b_ent + b_base + b_adv +
+                         b_asrc + b_aslot + b_arow + b_arrived + 256;
 
     std::vector<char> stage(total, 0);
     size_t off = 0;
@@ -163,16 +163,15 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     const size_t o_runs = put(p.runs.data(), p.runs.size() * sizeof(Run), b_runs);
     const size_t o_stream =
         put(p.stream_items.data(), p.stream_items.size() * sizeof(StreamItem), b_stream);
-    const size_t o_casc =
-        put(p.cascade_items.data(), p.cascade_items.size() * sizeof(CascadeItem), b_casc);
+    const size_t o_units = put(p.units.data(), p.units.size() * sizeof(UnitSlot), b_units);
     const size_t o_wide =
         put(p.wide_items.data(), p.wide_items.size() * sizeof(CascadeItem), b_wide);
-    const size_t o_map = put(p.wg_map.data(), p.wg_map.size() * sizeof(int32_t), b_map);
     const size_t o_ent = put(p.ent_order.data(), p.ent_order.size() * sizeof(int32_t), b_ent);
     const size_t o_base = put(p.part_base.data(), p.part_base.size() * sizeof(int32_t), b_base);
     const size_t o_ebase = put(p.ent_base.data(), p.ent_base.size() * sizeof(int32_t), b_ent);
     const size_t o_adv = put(p.adv.data(), p.adv.size() * sizeof(AdvEntry), b_adv);
     const size_t o_asrc = put(p.adv_src.data(), p.adv_src.size() * sizeof(int32_t), b_asrc);
+    const size_t o_aslot = put(p.adv_slots.data(), p.adv_slots.size() * sizeof(int32_t), b_aslot);
     const size_t o_arow = put(p.adv_last_row.data(), p.adv_last_row.size() * sizeof(int64_t), b_arow);
     const size_t o_arrived = put(nullptr, 0, b_arrived);
 
@@ -196,14 +195,14 @@ ets_status upload_plan_unguarded(ets_ctx* c) {
     }
     c->d_runs = reinterpret_cast<Run*>(c->d_buf + o_runs);
     c->d_stream = reinterpret_cast<StreamItem*>(c->d_buf + o_stream);
-    c->d_cascade = reinterpret_cast<CascadeItem*>(c->d_buf + o_casc);
+    c->d_units = reinterpret_cast<UnitSlot*>(c->d_buf + o_units);
     c->d_wide = reinterpret_cast<CascadeItem*>(c->d_buf + o_wide);
-    c->d_wg_map = reinterpret_cast<int32_t*>(c->d_buf + o_map);
     c->d_ent_order = reinterpret_cast<int32_t*>(c->d_buf + o_ent);
     c->d_part_base = reinterpret_cast<int32_t*>(c->d_buf + o_base);
     c->d_ent_base = reinterpret_cast<int32_t*>(c->d_buf + o_ebase);
     c->d_adv = reinterpret_cast<AdvEntry*>(c->d_buf + o_adv);
     c->d_adv_src = reinterpret_cast<int32_t*>(c->d_buf + o_asrc);
+    c->d_adv_slots = reinterpret_cast<int32_t*>(c->d_buf + o_aslot);
     c->d_adv_last_row = reinterpret_cast<int64_t*>(c->d_buf + o_arow);
     c->d_arrived = reinterpret_cast<int32_t*>(c->d_buf + o_arrived);
     return ETS_OK;
@@ -274,7 +273,6 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
     const int g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
     // grid: x = kv head, y = workgroup (at most 65535 per launch): first the items that
     // take a workgroup each, then the small ones, four to a workgroup
-    const int64_t n_single = c->plan.n_single;
     const int64_t n_wgs = (int64_t)c->plan.wg_map.size();
     MergeTail tail{};
     if (c->plan.fused) {
@@ -297,7 +295,7 @@ void launch_tree_attn(const ets_ctx* c, const LaunchArgs& a) {
                                  : (fp8 ? tree_attn_kernel<true, false> : tree_attn_kernel<false, false>));
         hipLaunchKernelGGL(kernel, dim3((unsigned)c->shape.n_kv_heads, ny), dim3(256), 0, a.stream,
                            a.k, a.v, a.pool_tokens, static_cast<const bf16_t*>(a.q), c->d_runs,
-                           c->d_cascade, c->d_wg_map, (int)y0, (int)n_single, (int)n_items,
+                           c->d_units, (int)y0,
                            c->d_ent_order, c->d_ent_base, g_shift, c->scale * 1.4426950408889634f,
                            c->k_scales, a.ws_o, a.ws_ml, tail);
     }
@@ -610,6 +608,11 @@ ets_status ets_plan_advance(ets_ctx* ctx, void* hip_stream, int32_t* replanned) 
             const int n = (int)p.adv.size();
             hipLaunchKernelGGL(advance_runs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
                                stream, ctx->d_runs, ctx->d_adv, n, (int)p.piece, advances_before);
+            const int n_slots = (int)p.adv_slots.size();
+            if (n_slots > 0)
+                hipLaunchKernelGGL(refresh_units_kernel, dim3((unsigned)((n_slots + 255) / 256)),
+                                   dim3(256), 0, stream, ctx->d_units, ctx->d_adv_slots, n_slots,
+                                   ctx->d_runs);
             if (hipGetLastError() != hipSuccess) return ETS_ERR_HIP;
             ctx->last_stream = stream;
             ctx->stream_used = true;

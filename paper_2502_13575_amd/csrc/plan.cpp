@@ -121,6 +121,51 @@ bool cut_runs(Plan& p, const std::vector<Run>& src, int64_t tokens, int64_t cap,
     return ok;
 }
 
+// Fills the slot's copies of its item's steps from the step lists.  Returns whether one of
+// them is a run that an advance may extend.
+bool fill_unit_steps(const Plan& p, UnitSlot& u, int wave, const std::vector<char>* grows) {
+    bool may_grow = false;
+    Run* dst[2] = {&u.first, &u.second};
+    for (int j = 0; j < 2; ++j) {
+        const int k = unit_step_index(u.item, wave, j);
+        const int64_t r = (int64_t)u.item.run_begin + k;
+        if (k < 0 || r >= u.item.run_end) {
+            *dst[j] = Run{0, 0, 0};
+            continue;
+        }
+        *dst[j] = p.runs[(size_t)r];
+        if (grows) may_grow = may_grow || (*grows)[(size_t)r];
+    }
+    return may_grow;
+}
+
+// The table the matrix-core kernel starts from (see UnitSlot), and the slots whose copies
+// of steps an advance has to refresh.
+void build_units(Plan& p) {
+    const size_t n_units = p.wg_map.size();
+    p.units.assign(4 * n_units, UnitSlot{});  // zero: n_ent = 0, nothing to do
+    p.adv_slots.clear();
+    std::vector<char> grows(p.runs.size(), 0);
+    for (const AdvEntry& e : p.adv) grows[(size_t)e.r_last] = grows[(size_t)e.r_spare] = 1;
+    const int64_t n_items = (int64_t)p.cascade_items.size();
+    for (size_t y = 0; y < n_units; ++y) {
+        const int32_t code = p.wg_map[y];
+        for (int w = 0; w < 4; ++w) {
+            const int64_t idx = code >= 0 ? code : p.n_single + 4 * (-(int64_t)code - 1) + w;
+            if (idx >= n_items) continue;
+            UnitSlot& u = p.units[4 * y + (size_t)w];
+            u.item = p.cascade_items[(size_t)idx];
+            u.item.wave_item = code < 0 ? 1 : 0;
+            if (fill_unit_steps(p, u, w, &grows)) p.adv_slots.push_back((int32_t)(4 * y + (size_t)w));
+        }
+    }
+}
+
+// After an advance: the unit table's copies follow the step lists.
+void refresh_units(Plan& p) {
+    for (int32_t slot : p.adv_slots) fill_unit_steps(p, p.units[(size_t)slot], slot & 3, nullptr);
+}
+
 ets_status validate(const ets_tree& t) {
     if (t.n_nodes < 0 || t.n_leaves < 0) return ETS_ERR_INVALID_ARG;
     if (t.n_nodes > 0 && (!t.parent || !t.tok_offset || !t.n_tokens)) return ETS_ERR_INVALID_ARG;
@@ -504,7 +549,10 @@ ets_status build(const ets_shape& shape, const PlanOptions& opt, const ets_tree&
         }
     }
 
-    if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max()) return ETS_ERR_UNSUPPORTED;
+    if (p.runs.size() >= (size_t)std::numeric_limits<int32_t>::max() ||
+        p.wg_map.size() >= (size_t)std::numeric_limits<int32_t>::max() / 16)
+        return ETS_ERR_UNSUPPORTED;
+    build_units(p);
     {
         std::vector<int32_t> first(N, -1);
         p.adv_node.clear();
@@ -575,6 +623,7 @@ bool advance_in_place(Plan& plan) {
             spare.n += 1;
         }
     }
+    refresh_units(plan);
     plan.advances += 1;
     plan.adv_room -= 1;
     advance_tree(plan);
@@ -707,6 +756,33 @@ bool check_plan(const Plan& p, const ets_shape& shape, PlanCheck& out) {
             if (run.n > 0) {
                 bad(run.tok + run.n > p.stats.min_pool_tokens);
                 out.max_pool_row = std::max(out.max_pool_row, run.tok + run.n - 1);
+            }
+        }
+    }
+    // the unit table says what the launch order and the step lists say
+    bad(p.units.size() != 4 * p.wg_map.size());
+    for (size_t y = 0; y < p.wg_map.size() && 4 * y + 3 < p.units.size(); ++y) {
+        const int32_t code = p.wg_map[y];
+        for (int w = 0; w < 4; ++w) {
+            const UnitSlot& u = p.units[4 * y + (size_t)w];
+            const int64_t idx = code >= 0 ? code : p.n_single + 4 * (-(int64_t)code - 1) + w;
+            if (idx < 0 || idx >= (int64_t)p.cascade_items.size()) {
+                bad(u.item.n_ent != 0);
+                continue;
+            }
+            const CascadeItem& it = p.cascade_items[(size_t)idx];
+            bad(u.item.run_begin != it.run_begin || u.item.run_end != it.run_end ||
+                u.item.ent_begin != it.ent_begin || u.item.n_ent != it.n_ent ||
+                u.item.slot_off != it.slot_off || u.item.sole_reader != it.sole_reader ||
+                u.item.wave_item != (code < 0 ? 1 : 0));
+            const Run* held[2] = {&u.first, &u.second};
+            for (int j = 0; j < 2; ++j) {
+                const int k = unit_step_index(u.item, w, j);
+                const int64_t r = (int64_t)it.run_begin + k;
+                if (k >= 0 && r < it.run_end && r < n_runs)
+                    bad(held[j]->tok != p.runs[(size_t)r].tok || held[j]->n != p.runs[(size_t)r].n);
+                else
+                    bad(held[j]->n != 0);
             }
         }
     }

@@ -40,8 +40,29 @@ struct CascadeItem {
     int32_t slot_off;
     int32_t n_tokens;
     int32_t sole_reader;  // 1: no other item reads these rows
-    int32_t pad1;
+    int32_t wave_item;    // 1: a small item walked by one wavefront (set in the unit table)
 };
+
+// What a wavefront of the matrix-core kernel starts from, in launch order: wave w of
+// workgroup y reads units[4 y + w]: its work item (n_ent = 0: nothing to do) and the step
+// it fetches first (n = 0: none), so that the first tile can be requested after a single
+// table read.  Item of a workgroup: four copies, `first` = step w / 2 of the item (the wave
+// fetches half w % 2 of it), `second` unused.  Small item of a wave: `first` = its step 0,
+// `second` = its step 1.  64 bytes.
+struct UnitSlot {
+    CascadeItem item;
+    Run first;
+    Run second;
+};
+
+// Step j of the slot's item as the unit table holds it: 0 = first, 1 = second (-1: none).
+// Used by the host planner and by the kernel that refreshes the table after an advance.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int unit_step_index(const CascadeItem& item, int wave, int j) {
+    return item.wave_item ? j : (j == 0 ? wave >> 1 : -1);
+}
 
 // Where a growing node's next token goes (decode-step advance): one record per copy of
 // the node's tail in Plan::runs.  The token joins run `r_last` if that run ends at the
@@ -105,6 +126,9 @@ struct Plan {
     std::vector<int32_t> wg_map;      // launch order of the matrix-core kernel: workgroup i takes
                                       // item wg_map[i] when that is >= 0, else the four small
                                       // items of group -wg_map[i] - 1 (n_single + 4 g ..)
+    std::vector<UnitSlot> units;      // [4 * wg_map.size()] what the kernel reads: see UnitSlot
+    std::vector<int32_t> adv_slots;   // slots of `units` whose copies of the first steps hold a
+                                      // run that an advance may extend (refreshed after it)
     // decode-step advance: every distinct node of leaf_node grows by one token
     std::vector<AdvEntry> adv;        // tails to extend
     std::vector<int32_t> adv_node;    // distinct leaf nodes, in order of first appearance

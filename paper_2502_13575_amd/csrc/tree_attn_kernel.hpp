@@ -262,8 +262,7 @@ template <bool FP8, bool FUSED, int D = 128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void tree_attn_kernel(
     const void* __restrict__ k_pool, const void* __restrict__ v_pool, int64_t pool_tokens,
     const bf16_t* __restrict__ q, const Run* __restrict__ steps,
-    const CascadeItem* __restrict__ items, const int32_t* __restrict__ wg_map, int wg_base,
-    int n_single, int n_items,
+    const UnitSlot* __restrict__ units, int unit_base,
     const int32_t* __restrict__ ent_order, const int32_t* __restrict__ ent_base, int g_shift,
     float scale_log2e_base, HeadScales k_scales,
     float* __restrict__ ws_o, float2* __restrict__ ws_ml, MergeTail tail) {
@@ -297,11 +296,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
     const float scale_log2e = FP8 ? scale_log2e_base * k_scales.s[h] : scale_log2e_base;
     // A workgroup takes one item, or four small items, one per wave, which then works alone
     // (no barrier below this point on that path); the planner's launch order says which.
-    const int code = wg_map[wg_base + (int)blockIdx.y];  // uniform: a scalar load
-    const bool wave_item = code < 0;
-    const int item_idx = wave_item ? n_single + 4 * (-code - 1) + w : code;
-    if (item_idx >= n_items) return;
-    const CascadeItem it = items[item_idx];
+    // One table read (uniform per wave: scalar loads) brings the item and the step this wave
+    // fetches first, in launch order.
+    const UnitSlot* my_unit = units + 4 * (unit_base + (int)blockIdx.y) + w;
+    const CascadeItem it = my_unit->item;
+    const Run first_step = my_unit->first;
+    const bool wave_item = it.wave_item != 0;
+    if (it.n_ent == 0) return;
     const int G = 1 << g_shift;
     const int n_q_heads = n_kv_heads << g_shift;
     const int R = it.n_ent << g_shift;
@@ -546,7 +547,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         u32x4_t* ksw = smem + w * (16 * KROW + NX * 32);
         u32x2_t* vsw = reinterpret_cast<u32x2_t*>(ksw + 16 * KROW);
         auto unit_rows = [&](int u, int64_t& tok) {
-            const Run sd = my_steps[u >> 1];  // uniform: scalar load
+            // steps 0 and 1 stand in the unit table; the others: uniform, a scalar load
+            const Run sd = u < 2 ? first_step : u < 4 ? my_unit->second : my_steps[u >> 1];
             tok = sd.tok + 16 * (u & 1);
             return min(16, max(0, sd.n - 16 * (u & 1)));
         };
@@ -609,7 +611,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void t
         return;
     }
 
-    Run sd_loaded = sw < n_steps ? my_steps[sw] : Run{0, 0, 0};  // descriptor of the loads in flight
+    // descriptor of the loads in flight: the wave's step of the first tile came with the
+    // item (a step the item does not have reads n = 0 there)
+    Run sd_loaded = first_step;
     if (rowpar && !it.sole_reader)
         issue_loads(sd_loaded, std::integral_constant<int, 0>{});
     else
